@@ -1,0 +1,210 @@
+"""CPU oracle for the SNIP quantized linear-layer path.  TEST INFRASTRUCTURE ONLY.
+
+A thin ctypes loader around ``snip_oracle.c`` (plain C, IEEE double and integers).  Only
+the tests, the smoke check and the benchmark's CPU-baseline leg may import this package;
+the GPU library and its Python binding never do, and the two share no code.
+
+Passages followed (SNIP, arXiv 2602.01410): Sec. 2.3 (scaling by the block maximum and the
+cast to FPX), Sec. 2.2 (which tensors are quantized before which GEMM), Sec. 4.1 / 4.3.1
+(shapes of X, W, dY), Sec. 3.1 Step 1 and Sec. 5.3 (Frobenius-norm statistics and their
+row-wise form).  The paper prints no worked numeric example for this path; the pins are the
+closed forms, enumerations and brute-force checks in ``tests/test_oracle_*.py``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "snip_oracle.c")
+_LIB = os.path.join(_HERE, "libsnip_oracle.so")
+
+FP8, FP4 = 0, 1            # element formats: E4M3, E2M1
+ROW, COL = 0, 1            # direction of the 32-element tiles in the source matrix
+NO_OVERFLOW, FLOOR = 0, 1  # power-of-two scale rules
+TILE = 32
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i64, dbl, ci, u16 = ctypes.c_int64, ctypes.c_double, ctypes.c_int, ctypes.c_uint16
+        vp = ctypes.c_void_p
+        lib.oracle_bf16_to_f64.restype = dbl
+        lib.oracle_bf16_to_f64.argtypes = [u16]
+        lib.oracle_decode.restype = dbl
+        lib.oracle_decode.argtypes = [ci, ctypes.c_uint]
+        lib.oracle_fmt_max.restype = dbl
+        lib.oracle_fmt_max.argtypes = [ci]
+        lib.oracle_encode_rne.restype = ctypes.c_uint
+        lib.oracle_encode_rne.argtypes = [ci, dbl]
+        lib.oracle_scale_byte.restype = ctypes.c_uint
+        lib.oracle_scale_byte.argtypes = [ci, ci, dbl]
+        lib.oracle_quantize.restype = ci
+        lib.oracle_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp]
+        lib.oracle_dequantize.restype = ci
+        lib.oracle_dequantize.argtypes = [vp, vp, i64, i64, ci, vp]
+        lib.oracle_fake_quant.restype = ci
+        lib.oracle_fake_quant.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp]
+        for name in ("oracle_gemm_fwd", "oracle_gemm_dgrad", "oracle_gemm_wgrad"):
+            fn = getattr(lib, name)
+            fn.restype = ci
+            fn.argtypes = [vp, vp, i64, i64, i64, vp]
+        lib.oracle_stats.restype = ci
+        lib.oracle_stats.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _bf16_2d(x) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    if x.ndim != 2:
+        raise ValueError("expected a 2-D array of bf16 bit patterns (uint16)")
+    return x
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"oracle {what}: bad argument")
+
+
+# ---- scalar pieces -------------------------------------------------------------------
+
+def bf16_to_f64(bits: int) -> float:
+    return _load().oracle_bf16_to_f64(int(bits) & 0xFFFF)
+
+
+def decode(fmt: int, code: int) -> float:
+    """Value of one element code."""
+    return _load().oracle_decode(fmt, int(code))
+
+
+def fmt_max(fmt: int) -> float:
+    return _load().oracle_fmt_max(fmt)
+
+
+def encode_rne(fmt: int, v: float) -> int:
+    """Code of the grid value nearest to v (ties to even mantissa, saturating, sign kept)."""
+    return int(_load().oracle_encode_rne(fmt, float(v)))
+
+
+def scale_byte(fmt: int, rule: int, amax: float) -> int:
+    """E8M0 byte of the block scale for a block whose largest magnitude is amax."""
+    return int(_load().oracle_scale_byte(fmt, rule, float(amax)))
+
+
+# ---- tensors -------------------------------------------------------------------------
+
+def stored_shape(rows: int, cols: int, axis: int):
+    return (rows, cols) if axis == ROW else (cols, rows)
+
+
+def quantize(x_bf16_bits, fmt: int, axis: int = ROW, rule: int = NO_OVERFLOW):
+    """bf16 bits [rows, cols] -> (codes, scales) in the stored orientation.
+
+    codes: uint8 [SR, SC] (FP8) or [SR, SC//2] (FP4, even element in the low nibble);
+    scales: uint8 [SR, SC//32].  (SR, SC) = stored_shape(rows, cols, axis).
+    """
+    x = _bf16_2d(x_bf16_bits)
+    rows, cols = x.shape
+    sr, sc = stored_shape(rows, cols, axis)
+    codes = np.zeros((sr, sc if fmt == FP8 else sc // 2), dtype=np.uint8)
+    scales = np.zeros((sr, sc // TILE), dtype=np.uint8)
+    _check(_load().oracle_quantize(_ptr(x), rows, cols, cols, fmt, axis, rule,
+                                   _ptr(codes), _ptr(scales)), "quantize")
+    return codes, scales
+
+
+def dequantize(codes, scales, fmt: int) -> np.ndarray:
+    """Stored codes + scales -> float64 [SR, SC]."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.uint8)
+    sr = codes.shape[0]
+    sc = codes.shape[1] if fmt == FP8 else codes.shape[1] * 2
+    out = np.empty((sr, sc), dtype=np.float64)
+    _check(_load().oracle_dequantize(_ptr(codes), _ptr(scales), sr, sc, fmt, _ptr(out)),
+           "dequantize")
+    return out
+
+
+def fake_quant(x_bf16_bits, fmt: int, axis: int = ROW, rule: int = NO_OVERFLOW) -> np.ndarray:
+    """q(x) as float64 in the source orientation [rows, cols]."""
+    x = _bf16_2d(x_bf16_bits)
+    rows, cols = x.shape
+    out = np.empty((rows, cols), dtype=np.float64)
+    _check(_load().oracle_fake_quant(_ptr(x), rows, cols, cols, fmt, axis, rule, _ptr(out)),
+           "fake_quant")
+    return out
+
+
+def _f64_2d(a) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    if a.ndim != 2:
+        raise ValueError("expected a 2-D float64 array")
+    return a
+
+
+def gemm_fwd(Xq, Wq) -> np.ndarray:
+    """Y[M,N] = sum_k Xq[m,k] Wq[n,k]."""
+    X, W = _f64_2d(Xq), _f64_2d(Wq)
+    (M, K), (N, K2) = X.shape, W.shape
+    if K != K2:
+        raise ValueError("fwd: K mismatch")
+    Y = np.empty((M, N), dtype=np.float64)
+    _check(_load().oracle_gemm_fwd(_ptr(X), _ptr(W), M, N, K, _ptr(Y)), "gemm_fwd")
+    return Y
+
+
+def gemm_dgrad(dYq, Wq) -> np.ndarray:
+    """dX[M,K] = sum_n dYq[m,n] Wq[n,k]."""
+    dY, W = _f64_2d(dYq), _f64_2d(Wq)
+    (M, N), (N2, K) = dY.shape, W.shape
+    if N != N2:
+        raise ValueError("dgrad: N mismatch")
+    dX = np.empty((M, K), dtype=np.float64)
+    _check(_load().oracle_gemm_dgrad(_ptr(dY), _ptr(W), M, N, K, _ptr(dX)), "gemm_dgrad")
+    return dX
+
+
+def gemm_wgrad(dYq, Xq) -> np.ndarray:
+    """dW[N,K] = sum_m dYq[m,n] Xq[m,k]."""
+    dY, X = _f64_2d(dYq), _f64_2d(Xq)
+    (M, N), (M2, K) = dY.shape, X.shape
+    if M != M2:
+        raise ValueError("wgrad: M mismatch")
+    dW = np.empty((N, K), dtype=np.float64)
+    _check(_load().oracle_gemm_wgrad(_ptr(dY), _ptr(X), M, N, K, _ptr(dW)), "gemm_wgrad")
+    return dW
+
+
+def stats(x_bf16_bits, axis: int = ROW, rule: int = NO_OVERFLOW, per_line: bool = False):
+    """(sum x^2, sum (q4(x)-x)^2, sum (q8(x)-x)^2) as float64[3]; with per_line=True also
+    the same sums per stored row, float64 [SR, 3]."""
+    x = _bf16_2d(x_bf16_bits)
+    rows, cols = x.shape
+    sr, _ = stored_shape(rows, cols, axis)
+    out = np.zeros(3, dtype=np.float64)
+    lines = np.zeros((sr, 3), dtype=np.float64) if per_line else None
+    _check(_load().oracle_stats(_ptr(x), rows, cols, cols, axis, rule, _ptr(out),
+                                _ptr(lines) if per_line else None), "stats")
+    return (out, lines) if per_line else out

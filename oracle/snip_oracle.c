@@ -1,0 +1,336 @@
+/*
+ * CPU oracle for the SNIP quantized linear-layer path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain definition of what the GPU library must compute.  It is
+ * used by the tests, by the smoke check and by the benchmark's CPU-baseline leg, and by
+ * nothing else.  It shares no code, header, table or constant with the HIP sources.
+ *
+ * What it follows (SNIP, arXiv 2602.01410):
+ *   - Sec. 2.3 "Quantization granularity": a tensor is scaled so that the largest
+ *     magnitude of a scaling group lands on the representable range of FPX, cast to FPX,
+ *     and scaled back afterwards (scale = FPX_MAX / max|x|, y = Op(Quant(x*scale))/scale).
+ *     Here the scaling group is a 1x32 tile and the scale is restricted to a power of two
+ *     (an E8M0 byte), which is the MX layout Sec. 2.3 "Quantization Format" adopts for
+ *     its FP4 E2M1 elements.
+ *   - Sec. 2.2 / Fig. "mixed precision training": inputs, weights and output gradients
+ *     are quantized before each of the three GEMMs of a linear layer.
+ *   - Sec. 4.1 / 4.3.1 notation: X in R^{M x K}, W in R^{N x K}, dY in R^{M x N}.
+ *   - Sec. 3.1 Step 1: Frobenius norms of the tensors and of their quantization error.
+ *   - Sec. 5.3 "Memory Overhead": the row-wise form of those norms.
+ *
+ * All arithmetic is IEEE double or integer.  Everything a bf16 tensor can hold, and every
+ * FP8/FP4 grid value times a power of two, is exact in double, so quantization here has
+ * no rounding other than the single round-to-nearest-even onto the FPX grid.
+ *
+ * Element formats (OCP MX flavours):
+ *   fmt 0 = FP8 E4M3: 1 sign, 4 exponent (bias 7), 3 mantissa bits, no infinities,
+ *           S.1111.111 is NaN, largest finite 448, smallest subnormal 2^-9.
+ *   fmt 1 = FP4 E2M1: 1 sign, 2 exponent (bias 1), 1 mantissa bit, values
+ *           {0, .5, 1, 1.5, 2, 3, 4, 6}.
+ * Scale rules for the power-of-two block scale 2^e (amax = m * 2^n, 1 <= m < 2):
+ *   rule 0 (no overflow): 2^e is the smallest power of two with amax / 2^e <= FPX_MAX,
+ *           i.e. the paper's scale rounded in the direction that keeps amax in range.
+ *   rule 1 (floor):       e = n - emax(FPX); elements that land above FPX_MAX saturate.
+ * Axis: 0 = the 32-element tiles run along a row of the source (contiguous elements),
+ *       1 = they run down a column; the quantized tensor is then stored transposed, so
+ *           that in both cases the stored matrix has its tiles along its rows.
+ *
+ * Parity pins for every function here live in tests/test_oracle_*.py (closed forms,
+ * enumeration of the grids, brute-force nearest-value search, tie tables, round trips,
+ * invariances, numpy's dgemm for the three products).  The paper prints no worked numeric
+ * example for this path, so no pin is a value quoted from the paper.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_TILE 32
+
+/* ---- format parameters ------------------------------------------------------------ */
+
+static int fmt_ebits(int fmt) { return fmt == 0 ? 4 : 2; }
+static int fmt_mbits(int fmt) { return fmt == 0 ? 3 : 1; }
+static int fmt_bias(int fmt)  { return fmt == 0 ? 7 : 1; }
+
+/* Largest finite magnitude: E4M3 gives up only the all-ones pattern to NaN, E2M1 nothing. */
+static unsigned fmt_max_code(int fmt) { return fmt == 0 ? 0x7Eu : 0x7u; }
+
+/* bf16 is the upper half of an IEEE single. */
+double oracle_bf16_to_f64(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* Value of an element code: sign, biased exponent E, mantissa field T.
+ * E == 0: subnormal, T * 2^(1 - bias - mbits); otherwise (1 + T/2^mbits) * 2^(E - bias). */
+double oracle_decode(int fmt, unsigned code)
+{
+    const int mb = fmt_mbits(fmt), eb = fmt_ebits(fmt), bias = fmt_bias(fmt);
+    const unsigned T = code & ((1u << mb) - 1u);
+    const unsigned E = (code >> mb) & ((1u << eb) - 1u);
+    const unsigned S = (code >> (mb + eb)) & 1u;
+    double mag;
+    if (fmt == 0 && E == 15u && T == 7u) return NAN;
+    if (E == 0u) mag = ldexp((double)T, 1 - bias - mb);
+    else         mag = ldexp(1.0 + ldexp((double)T, -mb), (int)E - bias);
+    return S ? -mag : mag;
+}
+
+double oracle_fmt_max(int fmt) { return oracle_decode(fmt, fmt_max_code(fmt)); }
+
+/* Round a real v onto the FPX grid: nearest value, ties to the even mantissa, magnitudes
+ * beyond the largest finite value saturate, the sign bit is kept (also on zero).
+ * The grid spacing around |v| is 2^(floor(log2|v|) - mbits), or the subnormal spacing
+ * below the smallest normal; |v| / spacing is rounded to an integer with ties to even,
+ * which is ties-to-even-mantissa because spacing * 2^mbits is the binade's lower end. */
+unsigned oracle_encode_rne(int fmt, double v)
+{
+    const int mb = fmt_mbits(fmt), eb = fmt_ebits(fmt), bias = fmt_bias(fmt);
+    const unsigned sign = signbit(v) ? 1u << (mb + eb) : 0u;
+    double a = fabs(v);
+    if (isnan(v)) return fmt == 0 ? 0x7Fu : 0u;
+    if (a > oracle_fmt_max(fmt)) return sign | fmt_max_code(fmt);
+    if (a == 0.0) return sign;
+    int p;
+    (void)frexp(a, &p);                 /* a = f * 2^p, 0.5 <= f < 1  =>  floor(log2 a) = p-1 */
+    int ex = p - 1;
+    if (ex < 1 - bias) ex = 1 - bias;   /* subnormal range shares the spacing of the first binade */
+    const int step_exp = ex - mb;
+    /* nearbyint under the default rounding mode rounds halves to the even integer */
+    double q = nearbyint(ldexp(a, -step_exp));    /* in [0, 2^(mb+1)] */
+    /* q counts grid steps from zero inside this binade's spacing; rebuild the value and
+     * re-derive its fields (q may have reached the next binade). */
+    double r = ldexp(q, step_exp);
+    if (r > oracle_fmt_max(fmt)) return sign | fmt_max_code(fmt);
+    if (r == 0.0) return sign;
+    (void)frexp(r, &p);
+    int rex = p - 1;
+    unsigned E, T;
+    if (rex < 1 - bias) {               /* subnormal result */
+        E = 0u;
+        T = (unsigned)ldexp(r, -(1 - bias - mb));
+    } else {
+        E = (unsigned)(rex + bias);
+        T = (unsigned)(ldexp(r, -rex + mb)) - (1u << mb);
+    }
+    return sign | (E << mb) | T;
+}
+
+/* Block scale exponent as the stored E8M0 byte (value 2^(byte-127)); 0xFF marks a block
+ * that holds a NaN or an infinity.  amax is the largest magnitude in the block. */
+unsigned oracle_scale_byte(int fmt, int rule, double amax)
+{
+    if (isnan(amax) || isinf(amax)) return 0xFFu;
+    int e;
+    if (amax == 0.0) {
+        e = -127;
+    } else {
+        int p;
+        double f = frexp(amax, &p);     /* amax = f * 2^p, f in [0.5, 1) */
+        double m = 2.0 * f;             /* in [1, 2) */
+        int n = p - 1;
+        double top = oracle_fmt_max(fmt);
+        int pt;
+        double ft = frexp(top, &pt);
+        int emax = pt - 1;              /* 8 for E4M3, 2 for E2M1 */
+        double mmax = 2.0 * ft;         /* 1.75 / 1.5 */
+        e = n - emax;
+        if (rule == 0 && m > mmax) e += 1;
+    }
+    if (e < -127) e = -127;
+    if (e > 127) e = 127;
+    return (unsigned)(e + 127);
+}
+
+/* ---- whole-tensor quantize -------------------------------------------------------- */
+
+/* Element (r, c) of the STORED matrix: for axis 0 the source itself, for axis 1 its
+ * transpose.  src is bf16 [rows_src][ld]. */
+static uint16_t stored_elem(const uint16_t* src, int64_t ld, int axis, int64_t r, int64_t c)
+{
+    return axis == 0 ? src[r * ld + c] : src[c * ld + r];
+}
+
+/* Quantize a bf16 matrix src[rows][cols] (row stride ld).
+ * Stored shape: SR x SC = rows x cols (axis 0) or cols x rows (axis 1); SC must be a
+ * multiple of 32.  codes: FP8 one byte per element [SR][SC]; FP4 two per byte
+ * [SR][SC/2], even element in the low nibble.  scales: [SR][SC/32] E8M0 bytes.
+ * Returns 0, or -1 on a bad argument. */
+int oracle_quantize(const uint16_t* src, int64_t rows, int64_t cols, int64_t ld,
+                    int fmt, int axis, int rule, uint8_t* codes, uint8_t* scales)
+{
+    if (!src || !codes || !scales) return -1;
+    if ((fmt != 0 && fmt != 1) || (axis != 0 && axis != 1) || (rule != 0 && rule != 1)) return -1;
+    if (rows < 0 || cols < 0 || ld < cols) return -1;
+    const int64_t SR = axis == 0 ? rows : cols;
+    const int64_t SC = axis == 0 ? cols : rows;
+    if (SC % ORACLE_TILE) return -1;
+    const int64_t nb = SC / ORACLE_TILE;
+    #pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < SR; ++r) {
+        for (int64_t b = 0; b < nb; ++b) {
+            double v[ORACLE_TILE];
+            double amax = 0.0;
+            int bad = 0;
+            for (int i = 0; i < ORACLE_TILE; ++i) {
+                v[i] = oracle_bf16_to_f64(stored_elem(src, ld, axis, r, b * ORACLE_TILE + i));
+                if (isnan(v[i]) || isinf(v[i])) bad = 1;
+                else if (fabs(v[i]) > amax) amax = fabs(v[i]);
+            }
+            unsigned sb = bad ? 0xFFu : oracle_scale_byte(fmt, rule, amax);
+            scales[r * nb + b] = (uint8_t)sb;
+            for (int i = 0; i < ORACLE_TILE; ++i) {
+                unsigned code = 0u;
+                if (!bad) code = oracle_encode_rne(fmt, ldexp(v[i], -((int)sb - 127)));
+                int64_t e = r * SC + b * ORACLE_TILE + i;
+                if (fmt == 0) {
+                    codes[e] = (uint8_t)code;
+                } else {
+                    /* two 4-bit codes per byte; bytes are owned by one thread (same r) */
+                    uint8_t* p = &codes[e >> 1];
+                    if ((e & 1) == 0) *p = (uint8_t)((*p & 0xF0u) | code);
+                    else              *p = (uint8_t)((*p & 0x0Fu) | (code << 4));
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* Stored codes + scales -> doubles [SR][SC] (same stored orientation). */
+int oracle_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t SR, int64_t SC,
+                      int fmt, double* out)
+{
+    if (!codes || !scales || !out) return -1;
+    if ((fmt != 0 && fmt != 1) || SR < 0 || SC < 0 || SC % ORACLE_TILE) return -1;
+    const int64_t nb = SC / ORACLE_TILE;
+    #pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < SR; ++r) {
+        for (int64_t c = 0; c < SC; ++c) {
+            unsigned sb = scales[r * nb + c / ORACLE_TILE];
+            int64_t e = r * SC + c;
+            unsigned code = fmt == 0 ? codes[e] : ((codes[e >> 1] >> ((e & 1) * 4)) & 0xFu);
+            out[e] = sb == 0xFFu ? NAN : ldexp(oracle_decode(fmt, code), (int)sb - 127);
+        }
+    }
+    return 0;
+}
+
+/* q(x) of Sec. 4.1 (q(x) = x + delta_x): quantize then dequantize, result in the SOURCE
+ * orientation out[rows][cols], whatever the tile axis. */
+int oracle_fake_quant(const uint16_t* src, int64_t rows, int64_t cols, int64_t ld,
+                      int fmt, int axis, int rule, double* out)
+{
+    const int64_t SR = axis == 0 ? rows : cols;
+    const int64_t SC = axis == 0 ? cols : rows;
+    if (rows < 0 || cols < 0) return -1;
+    size_t n = (size_t)rows * (size_t)cols;
+    uint8_t* codes = (uint8_t*)calloc(n ? n : 1, 1);
+    uint8_t* scales = (uint8_t*)calloc(n / ORACLE_TILE + 1, 1);
+    double* st = (double*)malloc((n ? n : 1) * sizeof(double));
+    int rc = -1;
+    if (codes && scales && st) {
+        rc = oracle_quantize(src, rows, cols, ld, fmt, axis, rule, codes, scales);
+        if (rc == 0) rc = oracle_dequantize(codes, scales, SR, SC, fmt, st);
+        if (rc == 0) {
+            for (int64_t r = 0; r < rows; ++r)
+                for (int64_t c = 0; c < cols; ++c)
+                    out[r * cols + c] = axis == 0 ? st[r * cols + c] : st[c * rows + r];
+        }
+    }
+    free(codes); free(scales); free(st);
+    return rc;
+}
+
+/* ---- the three products of a linear layer (Sec. 2.2; shapes of Sec. 4.1 / 4.3.1) ----
+ * Operands are q(.) values in double, in their natural orientations:
+ * X [M][K], W [N][K], dY [M][N].  One accumulator per output, k ascending. */
+
+int oracle_gemm_fwd(const double* X, const double* W, int64_t M, int64_t N, int64_t K, double* Y)
+{
+    if (!X || !W || !Y) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double s = 0.0;
+            for (int64_t k = 0; k < K; ++k) s += X[m * K + k] * W[n * K + k];
+            Y[m * N + n] = s;
+        }
+    return 0;
+}
+
+int oracle_gemm_dgrad(const double* dY, const double* W, int64_t M, int64_t N, int64_t K, double* dX)
+{
+    if (!dY || !W || !dX) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            double s = 0.0;
+            for (int64_t n = 0; n < N; ++n) s += dY[m * N + n] * W[n * K + k];
+            dX[m * K + k] = s;
+        }
+    return 0;
+}
+
+int oracle_gemm_wgrad(const double* dY, const double* X, int64_t M, int64_t N, int64_t K, double* dW)
+{
+    if (!dY || !X || !dW) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            double s = 0.0;
+            for (int64_t m = 0; m < M; ++m) s += dY[m * N + n] * X[m * K + k];
+            dW[n * K + k] = s;
+        }
+    return 0;
+}
+
+/* ---- Step-1 statistics (Sec. 3.1) -------------------------------------------------- */
+
+/* Squared Frobenius norms of x and of q(x) - x for both candidate formats, tiles along
+ * `axis`: out3 = { sum x^2, sum (q_fp4(x)-x)^2, sum (q_fp8(x)-x)^2 }.
+ * per_line (optional) holds the same three sums for every stored row, [SR][3]: one per
+ * source row for axis 0, one per source column for axis 1 (the row-wise form of
+ * Sec. 5.3).  Sums run in index order in double. */
+int oracle_stats(const uint16_t* src, int64_t rows, int64_t cols, int64_t ld,
+                 int axis, int rule, double* out3, double* per_line)
+{
+    if (!src || !out3) return -1;
+    if ((axis != 0 && axis != 1) || (rule != 0 && rule != 1)) return -1;
+    if (rows < 0 || cols < 0 || ld < cols) return -1;
+    const int64_t SR = axis == 0 ? rows : cols;
+    const int64_t SC = axis == 0 ? cols : rows;
+    if (SC % ORACLE_TILE) return -1;
+    size_t n = (size_t)rows * (size_t)cols;
+    double* q4 = (double*)malloc((n ? n : 1) * sizeof(double));
+    double* q8 = (double*)malloc((n ? n : 1) * sizeof(double));
+    double* line = (double*)calloc((size_t)(SR ? SR : 1) * 3, sizeof(double));
+    int rc = -1;
+    if (q4 && q8 && line) {
+        rc = oracle_fake_quant(src, rows, cols, ld, 1, axis, rule, q4);
+        if (rc == 0) rc = oracle_fake_quant(src, rows, cols, ld, 0, axis, rule, q8);
+    }
+    if (rc == 0) {
+        for (int64_t r = 0; r < SR; ++r) {
+            double s0 = 0.0, s4 = 0.0, s8 = 0.0;
+            for (int64_t c = 0; c < SC; ++c) {
+                int64_t sr = axis == 0 ? r : c, sc = axis == 0 ? c : r;   /* source coords */
+                double x = oracle_bf16_to_f64(src[sr * ld + sc]);
+                double d4 = q4[sr * cols + sc] - x;
+                double d8 = q8[sr * cols + sc] - x;
+                s0 += x * x; s4 += d4 * d4; s8 += d8 * d8;
+            }
+            line[r * 3 + 0] = s0; line[r * 3 + 1] = s4; line[r * 3 + 2] = s8;
+        }
+        out3[0] = out3[1] = out3[2] = 0.0;
+        for (int64_t r = 0; r < SR; ++r)
+            for (int j = 0; j < 3; ++j) out3[j] += line[r * 3 + j];
+        if (per_line) memcpy(per_line, line, (size_t)SR * 3 * sizeof(double));
+    }
+    free(q4); free(q8); free(line);
+    return rc;
+}
