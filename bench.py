@@ -1,0 +1,202 @@
+"""Benchmark of the SNIP quantized linear-layer hot path on one MI355X.
+
+A step is one pass of the whole path over one Llama-shaped transformer block's seven linear
+layers: every quantization the plan calls for (each distinct (tensor, format, axis) once, with
+the fused error statistics), the 21 GEMMs (fwd, dgrad, wgrad per linear) and the stand-alone
+dual-format statistics pass over every distinct tensor and axis.  Inputs are resident in HBM
+before timing starts.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+PEAK = {"fp4": 10.1e15, "fp8": 5.0e15, "hbm": 8.0e12}
+KERNEL_NAME = {(0, 0): "gemm_kernel<fp8,fp8>", (1, 1): "gemm_kernel<fp4,fp4>",
+               (0, 1): "gemm_kernel<fp8,fp4>", (1, 0): "gemm_kernel<fp4,fp8>"}
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=10)
+    p.add_argument("--warmup", type=int, default=3)
+    p.add_argument("--config", type=int, default=4, help="workload configuration 1..5 (default: Llama-7B-shaped layer)")
+    p.add_argument("--plan", type=str, default=None, help="fp4 | fp8 | mixNN | tensor (default: the config's mixed plan)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    return p.parse_args()
+
+
+class Layer:
+    """Device tensors, pre-allocated outputs and the launch list of one step."""
+
+    def __init__(self, cfg, plan, snip, wl):
+        self.cfg, self.plan, self.snip = cfg, plan, snip
+        dev = "cuda"
+
+        def up(bits):
+            return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+        t0 = time.time()
+        self.src = {}
+        for l in cfg.linears:
+            if ("X", l.x_group) not in self.src:
+                self.src[("X", l.x_group)] = up(wl.make_tensor(cfg, "X", l.x_group))
+            self.src[("W", l.name)] = up(wl.make_tensor(cfg, "W", l.name))
+            self.src[("dY", l.name)] = up(wl.make_tensor(cfg, "dY", l.name))
+        self.gen_seconds = time.time() - t0
+
+        max_r = max(t.shape[0] for t in self.src.values())
+        max_c = max(t.shape[1] for t in self.src.values())
+        self.ws = snip.alloc_workspace(max_r, max_c)
+        self.qjobs, self.q = [], {}       # distinct (src key, fmt, axis)
+        self.gjobs = []
+
+        def need(key, fmt, axis):
+            k = (key, fmt, axis)
+            if k not in self.q:
+                t = self.src[key]
+                sr, sc = (t.shape[0], t.shape[1]) if axis == snip.ROW else (t.shape[1], t.shape[0])
+                self.q[k] = snip.alloc_qtensor(sr, sc, fmt)
+                self.qjobs.append((k, snip.alloc_stats()))
+            return self.q[k]
+
+        M = cfg.M
+        for l, e in zip(cfg.linears, plan):
+            pc = snip.make_plan(e)
+            kx, kw, kdy = ("X", l.x_group), ("W", l.name), ("dY", l.name)
+            self.gjobs.append(("fwd", pc, need(kx, e[0], snip.ROW), need(kw, e[1], snip.ROW),
+                               torch.empty((M, l.N), dtype=torch.bfloat16, device=dev), 2 * M * l.N * l.K, (e[0], e[1])))
+            self.gjobs.append(("dgrad", pc, need(kdy, e[2], snip.ROW), need(kw, e[3], snip.COL),
+                               torch.empty((M, l.K), dtype=torch.bfloat16, device=dev), 2 * M * l.N * l.K, (e[2], e[3])))
+            self.gjobs.append(("wgrad", pc, need(kdy, e[4], snip.COL), need(kx, e[5], snip.COL),
+                               torch.empty((l.N, l.K), dtype=torch.bfloat16, device=dev), 2 * M * l.N * l.K, (e[4], e[5])))
+        self.sjobs = [(key, axis, snip.alloc_stats()) for key in self.src for axis in (snip.ROW, snip.COL)]
+        self.flops = sum(j[5] for j in self.gjobs)
+        self.q_bytes = sum(self.src[k[0]].numel() * (2 + (1.0 if k[1] == snip.FP8 else 0.5) + 1 / 32) for k, _ in self.qjobs)
+        self.s_bytes = sum(self.src[key].numel() * 2 for key, _, _ in self.sjobs)
+
+    def step(self, ev=None):
+        snip = self.snip
+        fn = {"fwd": snip.snip_gemm_fwd, "dgrad": snip.snip_gemm_dgrad, "wgrad": snip.snip_gemm_wgrad}
+
+        def timed(tag, f):
+            if ev is None:
+                f()
+                return
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            f()
+            b.record()
+            ev.append((tag, a, b))
+
+        for (key, fmt, axis), st in self.qjobs:
+            timed(("q", fmt, axis), lambda: snip.snip_quantize(self.src[key], fmt, axis, out=self.q[(key, fmt, axis)],
+                                                             stats=st, workspace=self.ws))
+        for name, pc, a, b, out, fl, fmts in self.gjobs:
+            timed(("g", fmts, fl), lambda: fn[name](pc, a, b, out=out))
+        for key, axis, st in self.sjobs:
+            timed(("s", axis), lambda: snip.snip_quant_error_stats(self.src[key], axis, out=st, workspace=self.ws))
+
+
+def cpu_baseline(cfg, wl):
+    """The oracle, as it stands, on a bounded sample: the first 256 tokens of the first linear,
+    all three GEMMs with their quantizations (fake-quant + fp64 product)."""
+    import oracle
+    lin = cfg.linears[0]
+    ms = min(256, cfg.M)
+    X = wl.make_tensor(cfg, "X", lin.x_group, 0, ms)
+    dY = wl.make_tensor(cfg, "dY", lin.name, 0, ms)
+    W = wl.make_tensor(cfg, "W", lin.name)
+    t0 = time.time()
+    y = oracle.gemm_fwd(oracle.fake_quant(X, oracle.FP4, oracle.ROW), oracle.fake_quant(W, oracle.FP4, oracle.ROW))
+    dx = oracle.gemm_dgrad(oracle.fake_quant(dY, oracle.FP4, oracle.ROW), oracle.fake_quant(W, oracle.FP4, oracle.COL))
+    dw = oracle.gemm_wgrad(oracle.fake_quant(dY, oracle.FP4, oracle.COL), oracle.fake_quant(X, oracle.FP4, oracle.COL))
+    dt = time.time() - t0
+    assert y.shape[0] == ms and dx.shape[0] == ms and dw.shape[0] == lin.N
+    flops = 3 * 2 * ms * lin.N * lin.K
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {ms} tokens of linear '{lin.name}' ({lin.N}x{lin.K}): 3 fake-quant GEMMs in fp64, "
+                      f"{flops:.3g} FLOP in {dt:.2f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    from paper_2602_01410_amd import snip, workloads as wl
+    snip._lib()
+    cfg = wl.CONFIGS[args.config]
+    plan_name = args.plan or next((p for p in cfg.plans if p.startswith("mix")), cfg.plans[0])
+    plan = wl.make_plan(cfg, plan_name)
+    torch.cuda.set_device(0)
+    layer = Layer(cfg, plan, snip, wl)
+
+    for _ in range(args.warmup):
+        layer.step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        layer.step(events)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+
+    # per-kernel figures from the HIP events recorded on the launch stream inside the timed region
+    agg = {}
+    for tag, a, b in events:
+        d = agg.setdefault(tag[0] if tag[0] != "g" else ("g", tag[1]), [0.0, 0, 0.0])
+        d[0] += a.elapsed_time(b) * 1e-3
+        d[1] += 1
+        if tag[0] == "g":
+            d[2] += tag[2]
+    gem = {k[1]: v for k, v in agg.items() if isinstance(k, tuple)}
+    dom = max(gem, key=lambda k: gem[k][0])
+    dsec, dn, dfl = gem[dom]
+    peak = PEAK["fp4"] if dom == (1, 1) else PEAK["fp8"]
+    achieved = dfl / dsec
+    gemm_sec = sum(v[0] for v in gem.values()) / args.steps
+    q_sec = agg["q"][0] / args.steps
+    s_sec = agg["s"][0] / args.steps
+    plan_peak = wl.plan_peak_flops(cfg, plan, PEAK["fp4"], PEAK["fp8"])
+    value = layer.flops / (ms_per_step * 1e-3) / 1e12
+
+    out = {
+        "metric": "TFLOP/s of mixed FP4/FP8 fwd+bwd linear GEMMs incl. quantize (% of MFMA peak)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp4_e2m1+fp8_e4m3 (fp32 accumulate, bf16 out)", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index}: {cfg.name}, {cfg.M} tokens, 7 linears x (fwd, dgrad, wgrad) "
+                               f"+ all quantizations + statistics pass", "plan": plan_name,
+                   "fp4_flop_fraction": wl.plan_fp4_fraction(cfg, plan), "layer_flop": layer.flops},
+        "pct_of_plan_peak": 100.0 * value * 1e12 / plan_peak,
+        "gemm_only_tflops": layer.flops / gemm_sec / 1e12,
+        "gemm_only_pct_of_plan_peak": 100.0 * layer.flops / gemm_sec / plan_peak,
+        "quantize_gbps": layer.q_bytes / q_sec / 1e9, "quantize_pct_hbm": 100.0 * layer.q_bytes / q_sec / PEAK["hbm"],
+        "stats_gbps": layer.s_bytes / s_sec / 1e9, "stats_pct_hbm": 100.0 * layer.s_bytes / s_sec / PEAK["hbm"],
+        "ms_gemm": gemm_sec * 1e3, "ms_quantize": q_sec * 1e3, "ms_stats": s_sec * 1e3,
+        "input_generation_s": layer.gen_seconds,
+        "roofline": {"bound": "mfma", "kernel": KERNEL_NAME[dom], "achieved": achieved / 1e12, "peak": peak / 1e12,
+                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                     "launches": dn, "avg_launch_us": dsec / dn * 1e6, "avg_flop_per_launch": dfl / dn},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,168 @@
+/*
+ * snip.h -- C ABI of the MI355X (gfx950) library for the quantized linear-layer hot path
+ * of SNIP (arXiv 2602.01410).
+ *
+ * The library implements what runs on every GPU in every training step of a mixed-precision
+ * linear layer (paper Sec. 2.2, Fig. "mixed precision training"): the inputs, weights and
+ * output gradients are quantized to FP8 or FP4 before each of the three GEMMs
+ *     forward      Y [M,N] = X [M,K] * W[N,K]^T
+ *     data grad    dX[M,K] = dY[M,N] * W[N,K]
+ *     weight grad  dW[N,K] = dY[M,N]^T * X[M,K]
+ * (shapes as in Sec. 4.1 / 4.3.1), the GEMM output stays in BF16, and the Frobenius norms of
+ * the tensors and of their quantization error are collected (Sec. 3.1, Step 1) as input to
+ * the loss- and weight-divergence estimates of Sec. 4.  Which format each operand uses is the
+ * per-layer decision of the paper's ILP (Sec. 4.2); here it arrives as a snip_layer_plan.
+ *
+ * Quantization (Sec. 2.3): every group of 32 consecutive elements along the contraction
+ * dimension of the consuming GEMM shares one power-of-two scale 2^e stored as an E8M0 byte
+ * (value 2^(byte-127)); elements are FP8 E4M3 (no infinities, max 448) or FP4 E2M1 (max 6),
+ * rounded to nearest with ties to the even mantissa.  This is the paper's
+ * "scale = FPX_MAX / max|x|" with the scale restricted to a power of two.
+ *
+ * General conventions
+ *  - Every pointer argument marked "device" is GPU memory owned by the caller; the library
+ *    never allocates, frees or keeps a pointer, and holds no global state.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *    enqueued on it; no call synchronizes.  Outputs are valid once the stream has reached
+ *    the end of the call.
+ *  - Arguments are validated on the host before anything is launched: a call that returns
+ *    an error has had no effect.  Errors are reported by return code only.
+ *  - Calls are re-entrant; calls on different streams may overlap if their outputs and
+ *    workspaces do not.
+ *  - Blocks that contain an infinity or a NaN get scale byte 0xFF and all-zero codes; no
+ *    error is raised for them.
+ */
+#ifndef SNIP_H
+#define SNIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SNIP_OK = 0,
+    SNIP_ERR_NULL = 1,       /* a required pointer is NULL */
+    SNIP_ERR_SHAPE = 2,      /* negative extent, blocked extent not a multiple of 32, ld too small */
+    SNIP_ERR_FORMAT = 3,     /* unknown enum value, or an operand's format differs from the plan */
+    SNIP_ERR_LAYOUT = 4,     /* misaligned pointer / leading dimension, operands' contraction extents differ */
+    SNIP_ERR_WORKSPACE = 5,  /* workspace missing or too small */
+    SNIP_ERR_HIP = 6         /* a kernel launch failed */
+} snip_status;
+
+typedef enum { SNIP_FP8_E4M3 = 0, SNIP_FP4_E2M1 = 1 } snip_fmt;
+
+/* Direction of the 32-element blocks in the SOURCE matrix. */
+typedef enum {
+    SNIP_AXIS_ROW = 0,       /* along a row (contiguous elements); stored matrix = source */
+    SNIP_AXIS_COL = 1        /* down a column; stored matrix = transpose of the source */
+} snip_axis;
+
+/* How the power-of-two scale 2^e is derived from the block maximum amax = m * 2^n, 1 <= m < 2. */
+typedef enum {
+    SNIP_SCALE_NO_OVERFLOW = 0, /* smallest 2^e with amax / 2^e <= FPX_MAX (the paper's scale,
+                                   rounded so that the block maximum stays representable) */
+    SNIP_SCALE_OCP_FLOOR = 1    /* e = n - emax(FPX); elements above FPX_MAX saturate */
+} snip_scale_rule;
+
+typedef enum { SNIP_OUT_BF16 = 0, SNIP_OUT_FP32 = 1 } snip_out_dtype;
+
+/* A quantized matrix in its stored orientation: `cols` is the blocked (contraction) extent.
+ *   codes : device. FP8: rows*cols bytes, row-major. FP4: rows*cols/2 bytes, row-major, element
+ *           2i in the low nibble and 2i+1 in the high nibble of byte i. 16-byte aligned.
+ *   scales: device. E8M0 bytes, [rows][cols/32] row-major.
+ *   rows, cols: extents of the stored matrix; cols must be a multiple of 32. */
+typedef struct {
+    void*    codes;
+    uint8_t* scales;
+    int64_t  rows, cols;
+    int32_t  fmt;            /* snip_fmt */
+} snip_qtensor;
+
+/* Element format of each operand of each GEMM of one linear layer.  The paper's option set
+ * (Sec. 4.2: one format each for inputs, weights, gradients) is the special case
+ * fwd_x == wgrad_x, fwd_w == dgrad_w, dgrad_dy == wgrad_dy. */
+typedef struct {
+    int32_t fwd_x, fwd_w, dgrad_dy, dgrad_w, wgrad_dy, wgrad_x;   /* snip_fmt each */
+} snip_layer_plan;
+
+/* Squared Frobenius norms (Sec. 3.1 Step 1): of the tensor, and of q(x) - x for both candidate
+ * formats.  A fused quantize call fills sum_sq and the chosen format's field and writes NaN
+ * into the other. */
+typedef struct { double sum_sq, err_sq_fp4, err_sq_fp8; } snip_stats;
+
+/* ---- sizes (host, pure) ------------------------------------------------------------- */
+
+/* Bytes of codes / scales for a stored matrix of rows x cols; 0 on a bad argument. */
+size_t snip_qtensor_code_bytes(int64_t rows, int64_t cols, snip_fmt fmt);
+size_t snip_qtensor_scale_bytes(int64_t rows, int64_t cols);
+
+/* Workspace (device bytes) sufficient for any call below on a source matrix of at most
+ * rows x cols, including per-line statistics. */
+size_t snip_workspace_bytes(int64_t rows, int64_t cols);
+
+/* ---- quantize (Sec. 2.3; which tensors: Sec. 2.2) ------------------------------------ */
+
+/* Quantize a bf16 matrix.
+ *   x     : device, bf16 [rows][ld], 16-byte aligned; ld >= cols, ld a multiple of 8.
+ *   axis  : SNIP_AXIS_ROW: blocks along rows; cols % 32 == 0; out is rows x cols.
+ *           SNIP_AXIS_COL: blocks down columns; rows % 32 == 0, cols even; out is stored
+ *           transposed, cols x rows, so that it equals quantize(transpose(x), ROW).
+ *   out   : host struct whose codes/scales point to device buffers of at least
+ *           snip_qtensor_code_bytes / snip_qtensor_scale_bytes; out->rows, out->cols and
+ *           out->fmt must already describe the stored matrix and `fmt`.
+ *   stats : device or NULL.  If given, the squared norms of x and of the quantization error
+ *           of `fmt` are produced by the same pass (then `workspace` is required).
+ *   workspace: device, >= snip_workspace_bytes(rows, cols) bytes, 16-byte aligned; may be
+ *           NULL when stats is NULL. */
+snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
+                          snip_fmt fmt, snip_axis axis, snip_scale_rule rule,
+                          const snip_qtensor* out, snip_stats* stats,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- the three GEMMs (Sec. 2.2; shapes Sec. 4.1 / 4.3.1) ----------------------------- */
+/* All three contract the stored `cols` of both operands: C[i][j] = sum_r A[i][r] * B[j][r]
+ * with a = code * 2^(scale-127), accumulated in fp32 and rounded once (nearest even) to the
+ * output type.  Operands must have equal cols (SNIP_ERR_LAYOUT otherwise) and the formats the
+ * plan names for that GEMM (SNIP_ERR_FORMAT otherwise).  The output is row-major with leading
+ * dimension ld_out (elements), 16-byte aligned rows.  `workspace` is reserved (may be NULL).
+ *
+ *   fwd  : Xq  = quantize(X,  ROW) [M,K],  Wq  = quantize(W,  ROW) [N,K]  ->  Y  [M,N]
+ *   dgrad: dYq = quantize(dY, ROW) [M,N],  Wq  = quantize(W,  COL) [K,N]  ->  dX [M,K]
+ *   wgrad: dYq = quantize(dY, COL) [N,M],  Xq  = quantize(X,  COL) [K,M]  ->  dW [N,K]   */
+snip_status snip_gemm_fwd(const snip_layer_plan* plan, const snip_qtensor* xq_row,
+                          const snip_qtensor* wq_row, void* y, int64_t ld_out,
+                          snip_out_dtype out_dtype, void* workspace, size_t workspace_bytes,
+                          void* stream);
+snip_status snip_gemm_dgrad(const snip_layer_plan* plan, const snip_qtensor* dyq_row,
+                            const snip_qtensor* wq_col, void* dx, int64_t ld_out,
+                            snip_out_dtype out_dtype, void* workspace, size_t workspace_bytes,
+                            void* stream);
+snip_status snip_gemm_wgrad(const snip_layer_plan* plan, const snip_qtensor* dyq_col,
+                            const snip_qtensor* xq_col, void* dw, int64_t ld_out,
+                            snip_out_dtype out_dtype, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/* ---- quantization-error statistics (Sec. 3.1 Step 1; row-wise form: Sec. 5.3) -------- */
+
+/* One read of a bf16 matrix; for blocks along `axis` produces the squared Frobenius norm of x
+ * and of q(x) - x for BOTH formats (the ILP needs the error of options that are not currently
+ * selected, Sec. 4.2).
+ *   out      : device, one snip_stats.
+ *   per_line : device or NULL; float [L][3] = {sum x^2, err^2 fp4, err^2 fp8} for every line of
+ *              the stored matrix: L = rows (one per source row) for AXIS_ROW, L = cols (one per
+ *              source column) for AXIS_COL.
+ *   workspace: device, required, >= snip_workspace_bytes(rows, cols). */
+snip_status snip_quant_error_stats(const void* x, int64_t rows, int64_t cols, int64_t ld,
+                                   snip_axis axis, snip_scale_rule rule,
+                                   snip_stats* out, float* per_line,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+const char* snip_status_string(snip_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SNIP_H */

@@ -1,0 +1,160 @@
+// C-ABI layer: argument validation and dispatch.  No kernel code here.
+#include "../../include/snip.h"
+#include "snip_internal.h"
+
+using namespace snip;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool valid_fmt(int f) { return f == SNIP_FP8_E4M3 || f == SNIP_FP4_E2M1; }
+
+snip_status check_source(const void* x, int64_t rows, int64_t cols, int64_t ld, int axis, int rule)
+{
+    if (!x && rows > 0 && cols > 0) return SNIP_ERR_NULL;   // an empty matrix may have no storage
+    if (axis != SNIP_AXIS_ROW && axis != SNIP_AXIS_COL) return SNIP_ERR_FORMAT;
+    if (rule != SNIP_SCALE_NO_OVERFLOW && rule != SNIP_SCALE_OCP_FLOOR) return SNIP_ERR_FORMAT;
+    if (rows < 0 || cols < 0 || ld < cols) return SNIP_ERR_SHAPE;
+    if (axis == SNIP_AXIS_ROW && cols % 32 != 0) return SNIP_ERR_SHAPE;
+    if (axis == SNIP_AXIS_COL && (rows % 32 != 0 || cols % 2 != 0)) return SNIP_ERR_SHAPE;
+    // kernels index work units with 32-bit integers
+    if (rows >= (int64_t)1 << 31 || cols >= (int64_t)1 << 31) return SNIP_ERR_SHAPE;
+    if ((rows + 31) / 32 * ((cols + 127) / 128) >= (int64_t)1 << 31) return SNIP_ERR_SHAPE;
+    if (rows * ((cols + 511) / 512) >= (int64_t)1 << 31) return SNIP_ERR_SHAPE;
+    if (!aligned16(x) || ld % 8 != 0) return SNIP_ERR_LAYOUT;
+    return SNIP_OK;
+}
+
+snip_status check_qtensor(const snip_qtensor* q)
+{
+    if (!q || !q->codes || !q->scales) return SNIP_ERR_NULL;
+    if (!valid_fmt(q->fmt)) return SNIP_ERR_FORMAT;
+    if (q->rows < 0 || q->cols <= 0 || q->cols % 32 != 0) return SNIP_ERR_SHAPE;
+    if (q->rows >= (int64_t)1 << 31 || q->cols >= (int64_t)1 << 31) return SNIP_ERR_SHAPE;
+    if (!aligned16(q->codes)) return SNIP_ERR_LAYOUT;
+    return SNIP_OK;
+}
+
+snip_status gemm(const snip_qtensor* a, int fmt_a, const snip_qtensor* b, int fmt_b, void* c, int64_t ldc,
+                 int out_dtype, void* stream)
+{
+    snip_status st = check_qtensor(a);
+    if (st != SNIP_OK) return st;
+    st = check_qtensor(b);
+    if (st != SNIP_OK) return st;
+    if (!c) return SNIP_ERR_NULL;
+    if (!valid_fmt(fmt_a) || !valid_fmt(fmt_b)) return SNIP_ERR_FORMAT;
+    if (out_dtype != SNIP_OUT_BF16 && out_dtype != SNIP_OUT_FP32) return SNIP_ERR_FORMAT;
+    if (a->fmt != fmt_a || b->fmt != fmt_b) return SNIP_ERR_FORMAT;
+    if (a->cols != b->cols) return SNIP_ERR_LAYOUT;
+    if (ldc < b->rows) return SNIP_ERR_SHAPE;
+    if ((a->rows + 127) / 128 * ((b->rows + 127) / 128) >= (int64_t)1 << 31) return SNIP_ERR_SHAPE;
+    const int64_t align_elems = out_dtype == SNIP_OUT_BF16 ? 8 : 4;
+    if (!aligned16(c) || ldc % align_elems != 0) return SNIP_ERR_LAYOUT;
+    GemmArgs g;
+    g.a_codes = (const uint8_t*)a->codes; g.a_scales = a->scales; g.fmt_a = fmt_a;
+    g.b_codes = (const uint8_t*)b->codes; g.b_scales = b->scales; g.fmt_b = fmt_b;
+    g.I = a->rows; g.J = b->rows; g.R = a->cols;
+    g.c = c; g.ldc = ldc; g.out_fp32 = out_dtype == SNIP_OUT_FP32;
+    return launch_gemm(g, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t snip_qtensor_code_bytes(int64_t rows, int64_t cols, snip_fmt fmt)
+{
+    if (rows < 0 || cols < 0 || cols % 32 != 0 || !valid_fmt(fmt)) return 0;
+    const size_t n = (size_t)rows * (size_t)cols;
+    return fmt == SNIP_FP8_E4M3 ? n : n / 2;
+}
+
+size_t snip_qtensor_scale_bytes(int64_t rows, int64_t cols)
+{
+    if (rows < 0 || cols < 0 || cols % 32 != 0) return 0;
+    return (size_t)rows * (size_t)(cols / 32);
+}
+
+size_t snip_workspace_bytes(int64_t rows, int64_t cols)
+{
+    if (rows < 0 || cols < 0) return 0;
+    return workspace_bytes(rows, cols);
+}
+
+snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_fmt fmt, snip_axis axis,
+                          snip_scale_rule rule, const snip_qtensor* out, snip_stats* stats, void* workspace,
+                          size_t workspace_bytes_, void* stream)
+{
+    if (!valid_fmt(fmt)) return SNIP_ERR_FORMAT;
+    snip_status st = check_source(x, rows, cols, ld, axis, rule);
+    if (st != SNIP_OK) return st;
+    if (!out) return SNIP_ERR_NULL;
+    if ((!out->codes || !out->scales) && rows > 0 && cols > 0) return SNIP_ERR_NULL;
+    if (out->fmt != (int32_t)fmt) return SNIP_ERR_FORMAT;
+    const int64_t sr = axis == SNIP_AXIS_ROW ? rows : cols, sc = axis == SNIP_AXIS_ROW ? cols : rows;
+    if (out->rows != sr || out->cols != sc) return SNIP_ERR_SHAPE;
+    if (!aligned16(out->codes)) return SNIP_ERR_LAYOUT;
+    if (stats) {
+        if (!workspace || workspace_bytes_ < workspace_bytes(rows, cols)) return SNIP_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return SNIP_ERR_LAYOUT;
+    }
+    QuantArgs a;
+    a.x = (const uint16_t*)x; a.rows = rows; a.cols = cols; a.ld = ld;
+    a.fmt = fmt; a.axis = axis; a.rule = rule;
+    a.codes = (uint8_t*)out->codes; a.scales = out->scales;
+    a.stats = (double*)stats; a.workspace = workspace;
+    return launch_quantize(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
+}
+
+snip_status snip_gemm_fwd(const snip_layer_plan* plan, const snip_qtensor* xq_row, const snip_qtensor* wq_row,
+                          void* y, int64_t ld_out, snip_out_dtype out_dtype, void*, size_t, void* stream)
+{
+    if (!plan) return SNIP_ERR_NULL;
+    return gemm(xq_row, plan->fwd_x, wq_row, plan->fwd_w, y, ld_out, out_dtype, stream);
+}
+
+snip_status snip_gemm_dgrad(const snip_layer_plan* plan, const snip_qtensor* dyq_row, const snip_qtensor* wq_col,
+                            void* dx, int64_t ld_out, snip_out_dtype out_dtype, void*, size_t, void* stream)
+{
+    if (!plan) return SNIP_ERR_NULL;
+    return gemm(dyq_row, plan->dgrad_dy, wq_col, plan->dgrad_w, dx, ld_out, out_dtype, stream);
+}
+
+snip_status snip_gemm_wgrad(const snip_layer_plan* plan, const snip_qtensor* dyq_col, const snip_qtensor* xq_col,
+                            void* dw, int64_t ld_out, snip_out_dtype out_dtype, void*, size_t, void* stream)
+{
+    if (!plan) return SNIP_ERR_NULL;
+    return gemm(dyq_col, plan->wgrad_dy, xq_col, plan->wgrad_x, dw, ld_out, out_dtype, stream);
+}
+
+snip_status snip_quant_error_stats(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_axis axis,
+                                   snip_scale_rule rule, snip_stats* out, float* per_line, void* workspace,
+                                   size_t workspace_bytes_, void* stream)
+{
+    snip_status st = check_source(x, rows, cols, ld, axis, rule);
+    if (st != SNIP_OK) return st;
+    if (!out) return SNIP_ERR_NULL;
+    if (!workspace || workspace_bytes_ < workspace_bytes(rows, cols)) return SNIP_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SNIP_ERR_LAYOUT;
+    StatsArgs a;
+    a.x = (const uint16_t*)x; a.rows = rows; a.cols = cols; a.ld = ld; a.axis = axis; a.rule = rule;
+    a.stats = (double*)out; a.per_line = per_line; a.workspace = workspace;
+    return launch_stats(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
+}
+
+const char* snip_status_string(snip_status s)
+{
+    switch (s) {
+        case SNIP_OK: return "ok";
+        case SNIP_ERR_NULL: return "null pointer";
+        case SNIP_ERR_SHAPE: return "bad shape";
+        case SNIP_ERR_FORMAT: return "bad format or enum";
+        case SNIP_ERR_LAYOUT: return "bad alignment or mismatched operands";
+        case SNIP_ERR_WORKSPACE: return "workspace missing or too small";
+        case SNIP_ERR_HIP: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,563 @@
+// Streaming kernels: bf16 -> block-scaled FP8/FP4 quantization (SNIP Sec. 2.3, applied to
+// the tensors Sec. 2.2 names) and the quantization-error statistics of Sec. 3.1 Step 1
+// (row-wise form: Sec. 5.3).  All of them are bound by HBM bandwidth: one 2-byte read per
+// element, 0.53 / 1.03 bytes written (FP4 / FP8), and a handful of VALU ops per element.
+//
+// A block of 32 elements is handled as follows.
+//   amax    : integer maximum of the bf16 magnitude bits (order-preserving for non-negative
+//             floats), packed 2 x u16 per VGPR.
+//   scale   : integer function of amax's exponent and mantissa fields (no log2).
+//   cast    : gfx950's v_cvt_scalef32_pk_{fp8,fp4}_bf16, which divides by the power of two
+//             in the scale operand's exponent field and rounds to nearest even.  The FP4
+//             form saturates; the FP8 form does not, so under the floor rule magnitudes are
+//             clamped to 448 * 2^e first (the no-overflow rule never exceeds it).
+//   error   : v_cvt_scalef32_pk_f32_{fp8,fp4} gives q(x) exactly in fp32; the difference to x
+//             (exact in fp32) is squared and summed in fp32 per lane, then per wave, and the
+//             per-wave partials are summed in double by a single-block kernel in fixed order.
+#include "snip_internal.h"
+
+namespace snip {
+namespace {
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short short2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+
+template <int FMT> struct Fmt;
+template <> struct Fmt<kFP8> { static constexpr int emax = 8; static constexpr unsigned mmax = 0x60; };  // 448 = 1.75 * 2^8
+template <> struct Fmt<kFP4> { static constexpr int emax = 2; static constexpr unsigned mmax = 0x40; };  // 6   = 1.5  * 2^2
+
+__device__ __forceinline__ unsigned pk_max_u16(unsigned a, unsigned b)
+{
+    return __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a),
+                                                                  __builtin_bit_cast(ushort2_t, b)));
+}
+__device__ __forceinline__ unsigned pk_min_u16(unsigned a, unsigned b)
+{
+    return __builtin_bit_cast(unsigned, __builtin_elementwise_min(__builtin_bit_cast(ushort2_t, a),
+                                                                  __builtin_bit_cast(ushort2_t, b)));
+}
+
+// Maximum over the four lanes of a quad (DPP quad_perm [1,0,3,2] then [2,3,0,1]).
+__device__ __forceinline__ unsigned quad_max(unsigned m)
+{
+    unsigned t = (unsigned)__builtin_amdgcn_update_dpp(0, (int)m, 0xB1, 0xF, 0xF, true);
+    m = m > t ? m : t;
+    t = (unsigned)__builtin_amdgcn_update_dpp(0, (int)m, 0x4E, 0xF, 0xF, true);
+    return m > t ? m : t;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// E8M0 byte from the 15 magnitude bits of the block maximum; 0xFF for Inf/NaN.
+template <int FMT, int RULE>
+__device__ __forceinline__ unsigned scale_byte(unsigned amax_bits)
+{
+    int b = (int)(amax_bits >> 7) - Fmt<FMT>::emax;
+    if (RULE == 0 && (amax_bits & 0x7Fu) > Fmt<FMT>::mmax) b += 1;
+    b = b < 0 ? 0 : b;
+    return amax_bits >= 0x7F80u ? 0xFFu : (unsigned)b;
+}
+
+// The conversion instructions read only the exponent field of their scale operand; the
+// mantissa bit set here keeps byte 0 (2^-127) from being an all-zero word.
+__device__ __forceinline__ float scale_operand(unsigned byte)
+{
+    return __uint_as_float((byte << 23) | 0x00400000u);
+}
+
+// Clamp both bf16 halves of w to magnitude <= 448 * 2^(byte-127) (floor rule, FP8 only).
+__device__ __forceinline__ unsigned clamp_fp8(unsigned w, unsigned byte)
+{
+    const unsigned lim = ((byte + 8u) << 7) | 0x60u;
+    const unsigned mag = pk_min_u16(w & 0x7FFF7FFFu, lim | (lim << 16));
+    return mag | (w & 0x80008000u);
+}
+
+// Two bf16 pairs (4 elements) -> 4 FP8 bytes.
+template <int RULE>
+__device__ __forceinline__ unsigned enc8(unsigned w0, unsigned w1, float sc, unsigned byte)
+{
+    if (RULE == 1) { w0 = clamp_fp8(w0, byte); w1 = clamp_fp8(w1, byte); }
+    short2_t r = {0, 0};
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(r, __builtin_bit_cast(bf16x2, w0), sc, false);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(r, __builtin_bit_cast(bf16x2, w1), sc, true);
+    return __builtin_bit_cast(unsigned, r);
+}
+
+// Four bf16 pairs (8 elements) -> 8 FP4 nibbles, element 0 in the lowest nibble.
+__device__ __forceinline__ unsigned enc4(unsigned w0, unsigned w1, unsigned w2, unsigned w3, float sc)
+{
+    unsigned r = 0;
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(bf16x2, w0), sc, 0);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(bf16x2, w1), sc, 1);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(bf16x2, w2), sc, 2);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(bf16x2, w3), sc, 3);
+    return r;
+}
+
+__device__ __forceinline__ void acc_err(float2_t q, unsigned w, float& s0, float& se, bool want_s0)
+{
+    const float xl = __uint_as_float(w << 16), xh = __uint_as_float(w & 0xFFFF0000u);
+    const float dl = q[0] - xl, dh = q[1] - xh;
+    se = fmaf(dl, dl, se);
+    se = fmaf(dh, dh, se);
+    if (want_s0) { s0 = fmaf(xl, xl, s0); s0 = fmaf(xh, xh, s0); }
+}
+
+// Error sums of 8 source elements w[0..3] against their FP8 codes c[0..1].
+__device__ __forceinline__ void err8(const unsigned* w, unsigned c0, unsigned c1, float sc,
+                                     float& s0, float& se, bool want_s0)
+{
+    acc_err(__builtin_amdgcn_cvt_scalef32_pk_f32_fp8(c0, sc, false), w[0], s0, se, want_s0);
+    acc_err(__builtin_amdgcn_cvt_scalef32_pk_f32_fp8(c0, sc, true),  w[1], s0, se, want_s0);
+    acc_err(__builtin_amdgcn_cvt_scalef32_pk_f32_fp8(c1, sc, false), w[2], s0, se, want_s0);
+    acc_err(__builtin_amdgcn_cvt_scalef32_pk_f32_fp8(c1, sc, true),  w[3], s0, se, want_s0);
+}
+__device__ __forceinline__ void err4(const unsigned* w, unsigned c, float sc,
+                                     float& s0, float& se, bool want_s0)
+{
+    acc_err(__builtin_amdgcn_cvt_scalef32_pk_f32_fp4(c, sc, 0), w[0], s0, se, want_s0);
+    acc_err(__builtin_amdgcn_cvt_scalef32_pk_f32_fp4(c, sc, 1), w[1], s0, se, want_s0);
+    acc_err(__builtin_amdgcn_cvt_scalef32_pk_f32_fp4(c, sc, 2), w[2], s0, se, want_s0);
+    acc_err(__builtin_amdgcn_cvt_scalef32_pk_f32_fp4(c, sc, 3), w[3], s0, se, want_s0);
+}
+
+// Magnitude bits of the largest of the 8 bf16 values in v (one lane's share of a block).
+__device__ __forceinline__ unsigned amax8(const uint4& v)
+{
+    unsigned m = pk_max_u16(pk_max_u16(v.x & 0x7FFF7FFFu, v.y & 0x7FFF7FFFu),
+                            pk_max_u16(v.z & 0x7FFF7FFFu, v.w & 0x7FFF7FFFu));
+    const unsigned lo = m & 0xFFFFu, hi = m >> 16;
+    return lo > hi ? lo : hi;
+}
+
+// ------------------------------------------------------------------------------------------
+// Row blocks.  A lane owns 8 consecutive elements (one 16-byte load), a quad owns a block, a
+// wave owns 512 consecutive elements of a row ("segment").  Four segments are in flight per
+// wave.  Loads and code stores are fully coalesced; the 16 scale bytes of a segment are
+// written by the first lane of each quad to 16 consecutive addresses.
+// ------------------------------------------------------------------------------------------
+constexpr int kSeg = 512;
+constexpr int kUnroll = 4;
+
+template <int FMT, int RULE, bool STATS>
+__global__ __launch_bounds__(256) void quant_row_kernel(const uint16_t* __restrict__ x, int rows,
+                                                        int cols, int64_t ld,
+                                                        uint8_t* __restrict__ codes,
+                                                        uint8_t* __restrict__ scales,
+                                                        float* __restrict__ partials)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    const int nwaves = gridDim.x * kWavesPerBlock;
+    const int spr = (cols + kSeg - 1) / kSeg;
+    const int units = rows * spr;
+    const int nblk = cols / kBlock;
+    float s0 = 0.f, se = 0.f;
+
+    for (int u0 = wave * kUnroll; u0 < units; u0 += nwaves * kUnroll) {
+        uint4 v[kUnroll];
+        int row[kUnroll], col[kUnroll];
+        bool act[kUnroll];
+#pragma unroll
+        for (int j = 0; j < kUnroll; ++j) {
+            const int u = u0 + j;
+            row[j] = u / spr;
+            col[j] = (u - row[j] * spr) * kSeg + lane * 8;
+            act[j] = u < units && col[j] < cols;
+            v[j] = make_uint4(0, 0, 0, 0);
+            if (act[j]) v[j] = *reinterpret_cast<const uint4*>(x + (int64_t)row[j] * ld + col[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < kUnroll; ++j) {
+            const unsigned am = quad_max(amax8(v[j]));
+            const unsigned byte = scale_byte<FMT, RULE>(am);
+            const float sc = scale_operand(byte);
+            const bool bad = byte == 0xFFu;
+            const unsigned w[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+            const int64_t e0 = (int64_t)row[j] * cols + col[j];
+            if (FMT == kFP8) {
+                unsigned c0 = enc8<RULE>(w[0], w[1], sc, byte), c1 = enc8<RULE>(w[2], w[3], sc, byte);
+                if (bad) { c0 = 0; c1 = 0; }
+                if (act[j]) *reinterpret_cast<uint2*>(codes + e0) = make_uint2(c0, c1);
+                if (STATS) err8(w, c0, c1, sc, s0, se, true);
+            } else {
+                unsigned c = enc4(w[0], w[1], w[2], w[3], sc);
+                if (bad) c = 0;
+                if (act[j]) *reinterpret_cast<unsigned*>(codes + (e0 >> 1)) = c;
+                if (STATS) err4(w, c, sc, s0, se, true);
+            }
+            if (act[j] && (lane & 3) == 0)
+                scales[(int64_t)row[j] * nblk + (col[j] >> 5)] = (uint8_t)byte;
+        }
+    }
+    if (STATS) {
+        s0 = wave_sum(s0);
+        se = wave_sum(se);
+        if (lane == 0) { partials[wave * 3 + 0] = s0; partials[wave * 3 + 1] = se; partials[wave * 3 + 2] = 0.f; }
+    }
+}
+
+// Statistics only, both formats, row blocks.  One wave walks whole rows so that the per-row
+// sums of Sec. 5.3 come out of the same pass.
+template <int RULE>
+__global__ __launch_bounds__(256) void stats_row_kernel(const uint16_t* __restrict__ x, int rows,
+                                                        int cols, int64_t ld,
+                                                        float* __restrict__ partials,
+                                                        float* __restrict__ per_line)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    const int nwaves = gridDim.x * kWavesPerBlock;
+    float t0 = 0.f, t4 = 0.f, t8 = 0.f;
+    for (int row = wave; row < rows; row += nwaves) {
+        const uint16_t* xr = x + (int64_t)row * ld;
+        float s0 = 0.f, s4 = 0.f, s8 = 0.f;
+        for (int c0 = 0; c0 < cols; c0 += kSeg * kUnroll) {
+            uint4 v[kUnroll];
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {
+                const int col = c0 + j * kSeg + lane * 8;
+                v[j] = make_uint4(0, 0, 0, 0);     // zeros quantize to zero: no contribution
+                if (col < cols) v[j] = *reinterpret_cast<const uint4*>(xr + col);
+            }
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {
+                const unsigned am = quad_max(amax8(v[j]));
+                const unsigned b8 = scale_byte<kFP8, RULE>(am), b4 = scale_byte<kFP4, RULE>(am);
+                const float sc8 = scale_operand(b8), sc4 = scale_operand(b4);
+                const unsigned w[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+                const unsigned c0_ = enc8<RULE>(w[0], w[1], sc8, b8), c1_ = enc8<RULE>(w[2], w[3], sc8, b8);
+                const unsigned c4 = enc4(w[0], w[1], w[2], w[3], sc4);
+                float dummy = 0.f;
+                err8(w, c0_, c1_, sc8, s0, s8, true);
+                err4(w, c4, sc4, dummy, s4, false);
+                if (b8 == 0xFFu) { s4 = __builtin_nanf(""); s8 = __builtin_nanf(""); }
+            }
+        }
+        s0 = wave_sum(s0); s4 = wave_sum(s4); s8 = wave_sum(s8);
+        if (per_line && lane == 0) {
+            per_line[(int64_t)row * 3 + 0] = s0; per_line[(int64_t)row * 3 + 1] = s4; per_line[(int64_t)row * 3 + 2] = s8;
+        }
+        t0 += s0; t4 += s4; t8 += s8;
+    }
+    if (lane == 0) { partials[wave * 3 + 0] = t0; partials[wave * 3 + 1] = t4; partials[wave * 3 + 2] = t8; }
+}
+
+// ------------------------------------------------------------------------------------------
+// Column blocks.  A lane owns two adjacent columns and reads them one dword per row: a wave
+// reads 256 contiguous bytes of each of 32 rows (one block per column), 32 independent loads
+// in flight.  The block maximum of a column never leaves the lane.  Rows are re-paired with
+// v_perm so that the conversion instructions pack elements that are adjacent in the
+// transposed output; each lane then stores 32 (FP8) or 16 (FP4) contiguous bytes per column.
+// A wave processes up to four vertically adjacent blocks back to back so that the 128-byte
+// lines of the output are completed within a short time.
+// ------------------------------------------------------------------------------------------
+constexpr int kColsPerWave = 128;
+constexpr int kRowBlocksPerUnit = 4;
+
+struct ColBlock {
+    unsigned lo[16], hi[16];   // bf16 pairs (row 2k, row 2k+1) of the lane's two columns
+    unsigned am_lo, am_hi;     // magnitude bits of each column's block maximum
+};
+
+__device__ __forceinline__ void load_col_block(const uint16_t* __restrict__ p, int64_t ld, bool act, ColBlock& b)
+{
+    unsigned v[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) v[i] = act ? *reinterpret_cast<const unsigned*>(p + (int64_t)i * ld) : 0u;
+    unsigned m = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) m = pk_max_u16(m, v[i] & 0x7FFF7FFFu);
+    b.am_lo = m & 0xFFFFu;
+    b.am_hi = m >> 16;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        b.lo[k] = __builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], 0x05040100u);
+        b.hi[k] = __builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], 0x07060302u);
+    }
+}
+
+template <int FMT, int RULE, bool STATS>
+__device__ __forceinline__ void quant_one_column(const unsigned* w, unsigned am, uint8_t* __restrict__ dst_codes,
+                                                 uint8_t* __restrict__ dst_scale, bool act, float& s0, float& se)
+{
+    const unsigned byte = scale_byte<FMT, RULE>(am);
+    const float sc = scale_operand(byte);
+    const bool bad = byte == 0xFFu;
+    if (FMT == kFP8) {
+        unsigned c[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            c[k] = enc8<RULE>(w[2 * k], w[2 * k + 1], sc, byte);
+            if (bad) c[k] = 0;
+        }
+        if (act) {
+            reinterpret_cast<uint4*>(dst_codes)[0] = make_uint4(c[0], c[1], c[2], c[3]);
+            reinterpret_cast<uint4*>(dst_codes)[1] = make_uint4(c[4], c[5], c[6], c[7]);
+        }
+        if (STATS) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) err8(w + 4 * k, c[2 * k], c[2 * k + 1], sc, s0, se, true);
+        }
+    } else {
+        unsigned c[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            c[k] = enc4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3], sc);
+            if (bad) c[k] = 0;
+        }
+        if (act) reinterpret_cast<uint4*>(dst_codes)[0] = make_uint4(c[0], c[1], c[2], c[3]);
+        if (STATS) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) err4(w + 4 * k, c[k], sc, s0, se, true);
+        }
+    }
+    if (act) *dst_scale = (uint8_t)byte;
+}
+
+template <int FMT, int RULE, bool STATS>
+__global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restrict__ x, int rows,
+                                                        int cols, int64_t ld,
+                                                        uint8_t* __restrict__ codes,
+                                                        uint8_t* __restrict__ scales,
+                                                        float* __restrict__ partials)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    const int nwaves = gridDim.x * kWavesPerBlock;
+    const int ncg = (cols + kColsPerWave - 1) / kColsPerWave;
+    const int nrb = rows / kBlock;
+    const int nru = (nrb + kRowBlocksPerUnit - 1) / kRowBlocksPerUnit;
+    const int units = ncg * nru;
+    float s0 = 0.f, se = 0.f;
+    for (int u = wave; u < units; u += nwaves) {
+        const int ru = u / ncg, cg = u - ru * ncg;
+        const int c = cg * kColsPerWave + lane * 2;
+        const bool act = c < cols;
+        const int rb_end = min(nrb, (ru + 1) * kRowBlocksPerUnit);
+        for (int rb = ru * kRowBlocksPerUnit; rb < rb_end; ++rb) {
+            ColBlock b;
+            load_col_block(x + (int64_t)rb * kBlock * ld + c, ld, act, b);
+            // stored matrix is [cols][rows]: column c becomes stored row c
+            const int64_t e_lo = (int64_t)c * rows + (int64_t)rb * kBlock;
+            const int64_t e_hi = e_lo + rows;
+            uint8_t* d_lo = codes + (FMT == kFP8 ? e_lo : (e_lo >> 1));
+            uint8_t* d_hi = codes + (FMT == kFP8 ? e_hi : (e_hi >> 1));
+            quant_one_column<FMT, RULE, STATS>(b.lo, b.am_lo, d_lo, scales + (int64_t)c * nrb + rb, act, s0, se);
+            quant_one_column<FMT, RULE, STATS>(b.hi, b.am_hi, d_hi, scales + (int64_t)(c + 1) * nrb + rb, act, s0, se);
+        }
+    }
+    if (STATS) {
+        s0 = wave_sum(s0);
+        se = wave_sum(se);
+        if (lane == 0) { partials[wave * 3 + 0] = s0; partials[wave * 3 + 1] = se; partials[wave * 3 + 2] = 0.f; }
+    }
+}
+
+// Statistics only, both formats, column blocks.  Grid: blockIdx.y = row split; a wave owns a
+// column group and the rows of its split, so per-column sums stay in the lane.
+template <int RULE>
+__global__ __launch_bounds__(256) void stats_col_kernel(const uint16_t* __restrict__ x, int rows,
+                                                        int cols, int64_t ld, int nsplit,
+                                                        float* __restrict__ partials,
+                                                        float* __restrict__ line_partials)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave_x = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    const int nwaves_x = gridDim.x * kWavesPerBlock;
+    const int split = blockIdx.y;
+    const int ncg = (cols + kColsPerWave - 1) / kColsPerWave;
+    const int nrb = rows / kBlock;
+    const int rb0 = (int)((int64_t)nrb * split / nsplit), rb1 = (int)((int64_t)nrb * (split + 1) / nsplit);
+    float t0 = 0.f, t4 = 0.f, t8 = 0.f;
+    for (int cg = wave_x; cg < ncg; cg += nwaves_x) {
+        const int c = cg * kColsPerWave + lane * 2;
+        const bool act = c < cols;
+        float a0[2] = {0.f, 0.f}, a4[2] = {0.f, 0.f}, a8[2] = {0.f, 0.f};
+        for (int rb = rb0; rb < rb1; ++rb) {
+            ColBlock b;
+            load_col_block(x + (int64_t)rb * kBlock * ld + c, ld, act, b);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const unsigned* w = h ? b.hi : b.lo;
+                const unsigned am = h ? b.am_hi : b.am_lo;
+                const unsigned b8 = scale_byte<kFP8, RULE>(am), b4 = scale_byte<kFP4, RULE>(am);
+                const float sc8 = scale_operand(b8), sc4 = scale_operand(b4);
+                float dummy = 0.f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const unsigned c0 = enc8<RULE>(w[4 * k], w[4 * k + 1], sc8, b8);
+                    const unsigned c1 = enc8<RULE>(w[4 * k + 2], w[4 * k + 3], sc8, b8);
+                    err8(w + 4 * k, c0, c1, sc8, a0[h], a8[h], true);
+                    const unsigned c4 = enc4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3], sc4);
+                    err4(w + 4 * k, c4, sc4, dummy, a4[h], false);
+                }
+                if (b8 == 0xFFu) { a4[h] = __builtin_nanf(""); a8[h] = __builtin_nanf(""); }
+            }
+        }
+        if (line_partials && act) {
+            float* lp = line_partials + ((int64_t)split * cols + c) * 3;
+            lp[0] = a0[0]; lp[1] = a4[0]; lp[2] = a8[0];
+            lp[3] = a0[1]; lp[4] = a4[1]; lp[5] = a8[1];
+        }
+        t0 += a0[0] + a0[1]; t4 += a4[0] + a4[1]; t8 += a8[0] + a8[1];
+    }
+    t0 = wave_sum(t0); t4 = wave_sum(t4); t8 = wave_sum(t8);
+    if (lane == 0) {
+        float* p = partials + ((int64_t)split * nwaves_x + wave_x) * 3;
+        p[0] = t0; p[1] = t4; p[2] = t8;
+    }
+}
+
+// Second stage: sum n per-wave partials [n][3] in double, fixed order, one block.
+// mode 0: out = {p0, p1, p2}; mode 1 (fused FP4): out = {p0, p1, NaN}; mode 2 (fused FP8): {p0, NaN, p1}.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partials, int n,
+                                                              int mode, double* __restrict__ out)
+{
+    __shared__ double sh[3][256];
+    double a[3] = {0.0, 0.0, 0.0};
+    for (int i = threadIdx.x; i < n; i += 256)
+        for (int j = 0; j < 3; ++j) a[j] += (double)partials[i * 3 + j];
+    for (int j = 0; j < 3; ++j) sh[j][threadIdx.x] = a[j];
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s)
+            for (int j = 0; j < 3; ++j) sh[j][threadIdx.x] += sh[j][threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double nan = __builtin_nan("");
+        if (mode == 0)      { out[0] = sh[0][0]; out[1] = sh[1][0]; out[2] = sh[2][0]; }
+        else if (mode == 1) { out[0] = sh[0][0]; out[1] = sh[1][0]; out[2] = nan; }
+        else                { out[0] = sh[0][0]; out[1] = nan;      out[2] = sh[1][0]; }
+    }
+}
+
+// Per-column sums: add the row splits in order.
+__global__ __launch_bounds__(256) void reduce_lines_kernel(const float* __restrict__ line_partials, int nsplit,
+                                                           int64_t n3, float* __restrict__ per_line)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n3) return;
+    double a = 0.0;
+    for (int s = 0; s < nsplit; ++s) a += (double)line_partials[(int64_t)s * n3 + i];
+    per_line[i] = (float)a;
+}
+
+constexpr size_t kPartialBytes = (size_t)kStreamWaves * 3 * sizeof(float);
+
+int col_splits(int64_t rows, int64_t cols, int* gx)
+{
+    const int ncg = (int)((cols + kColsPerWave - 1) / kColsPerWave);
+    int g = (ncg + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (g > kStreamBlocks) g = kStreamBlocks;
+    const int nrb = (int)(rows / kBlock);
+    int64_t want = kStreamWaves / ((int64_t)g * kWavesPerBlock);
+    if (want < 1) want = 1;
+    if (want > kMaxColSplits) want = kMaxColSplits;
+    if (want > nrb) want = nrb > 0 ? nrb : 1;
+    *gx = g;
+    return (int)want;
+}
+
+}  // namespace
+
+size_t workspace_bytes(int64_t rows, int64_t cols)
+{
+    (void)rows;
+    return kPartialBytes + (size_t)kMaxColSplits * (size_t)cols * 3 * sizeof(float);
+}
+
+template <int FMT, int RULE, bool STATS>
+static void launch_q(const QuantArgs& a, float* partials, hipStream_t s)
+{
+    if (a.axis == 0)
+        hipLaunchKernelGGL((quant_row_kernel<FMT, RULE, STATS>), dim3(kStreamBlocks), dim3(256), 0, s,
+                           a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, partials);
+    else
+        hipLaunchKernelGGL((quant_col_kernel<FMT, RULE, STATS>), dim3(kStreamBlocks), dim3(256), 0, s,
+                           a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, partials);
+}
+
+hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
+{
+    if (a.rows == 0 || a.cols == 0) {
+        if (a.stats) {
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, s,
+                               (const float*)a.workspace, 0, a.fmt == kFP4 ? 1 : 2, a.stats);
+        }
+        return hipGetLastError();
+    }
+    float* partials = (float*)a.workspace;
+    const bool st = a.stats != nullptr;
+    const int key = (a.fmt << 2) | (a.rule << 1) | (st ? 1 : 0);
+    switch (key) {
+        case 0: launch_q<kFP8, 0, false>(a, partials, s); break;
+        case 1: launch_q<kFP8, 0, true>(a, partials, s); break;
+        case 2: launch_q<kFP8, 1, false>(a, partials, s); break;
+        case 3: launch_q<kFP8, 1, true>(a, partials, s); break;
+        case 4: launch_q<kFP4, 0, false>(a, partials, s); break;
+        case 5: launch_q<kFP4, 0, true>(a, partials, s); break;
+        case 6: launch_q<kFP4, 1, false>(a, partials, s); break;
+        case 7: launch_q<kFP4, 1, true>(a, partials, s); break;
+        default: return hipErrorInvalidValue;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (st) {
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, s,
+                           (const float*)partials, kStreamWaves, a.fmt == kFP4 ? 1 : 2, a.stats);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+hipError_t launch_stats(const StatsArgs& a, hipStream_t s)
+{
+    float* partials = (float*)a.workspace;
+    if (a.rows == 0 || a.cols == 0) {
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, s, (const float*)partials, 0, 0, a.stats);
+        return hipGetLastError();
+    }
+    int npart;
+    if (a.axis == 0) {
+        if (a.rule == 0)
+            hipLaunchKernelGGL((stats_row_kernel<0>), dim3(kStreamBlocks), dim3(256), 0, s,
+                               a.x, (int)a.rows, (int)a.cols, a.ld, partials, a.per_line);
+        else
+            hipLaunchKernelGGL((stats_row_kernel<1>), dim3(kStreamBlocks), dim3(256), 0, s,
+                               a.x, (int)a.rows, (int)a.cols, a.ld, partials, a.per_line);
+        npart = kStreamWaves;
+    } else {
+        int gx;
+        const int nsplit = col_splits(a.rows, a.cols, &gx);
+        float* lines = a.per_line ? (float*)((char*)a.workspace + kPartialBytes) : nullptr;
+        if (a.rule == 0)
+            hipLaunchKernelGGL((stats_col_kernel<0>), dim3(gx, nsplit), dim3(256), 0, s,
+                               a.x, (int)a.rows, (int)a.cols, a.ld, nsplit, partials, lines);
+        else
+            hipLaunchKernelGGL((stats_col_kernel<1>), dim3(gx, nsplit), dim3(256), 0, s,
+                               a.x, (int)a.rows, (int)a.cols, a.ld, nsplit, partials, lines);
+        npart = gx * kWavesPerBlock * nsplit;
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        if (a.per_line) {
+            const int64_t n3 = a.cols * 3;
+            hipLaunchKernelGGL(reduce_lines_kernel, dim3((unsigned)((n3 + 255) / 256)), dim3(256), 0, s,
+                               (const float*)lines, nsplit, n3, a.per_line);
+        }
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, s, (const float*)partials, npart, 0, a.stats);
+    return hipGetLastError();
+}
+
+}  // namespace snip

@@ -1,0 +1,53 @@
+// Internal launcher interface between the C-ABI layer (api.hip) and the kernel files.
+// Nothing here is exported.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace snip {
+
+constexpr int kFP8 = 0;   // E4M3
+constexpr int kFP4 = 1;   // E2M1
+constexpr int kBlock = 32;  // elements per scale
+
+// Number of waves the streaming kernels are launched with; also the number of per-wave
+// partial-sum slots at the start of the workspace.  Fixed (not device dependent) so that
+// reductions run in the same order everywhere.
+constexpr int kStreamBlocks = 2048;
+constexpr int kWavesPerBlock = 4;
+constexpr int kStreamWaves = kStreamBlocks * kWavesPerBlock;
+constexpr int kMaxColSplits = 64;    // row splits of the column-statistics kernel
+
+struct QuantArgs {
+    const uint16_t* x;
+    int64_t rows, cols, ld;
+    int fmt, axis, rule;
+    uint8_t* codes;
+    uint8_t* scales;
+    double* stats;        // device snip_stats (3 doubles) or nullptr
+    void* workspace;
+};
+
+struct StatsArgs {
+    const uint16_t* x;
+    int64_t rows, cols, ld;
+    int axis, rule;
+    double* stats;        // device, 3 doubles
+    float* per_line;      // device [L][3] or nullptr
+    void* workspace;
+};
+
+struct GemmArgs {
+    const uint8_t* a_codes; const uint8_t* a_scales; int fmt_a;
+    const uint8_t* b_codes; const uint8_t* b_scales; int fmt_b;
+    int64_t I, J, R;      // C[I][J] = sum_r A[I][r] B[J][r]
+    void* c; int64_t ldc; int out_fp32;
+};
+
+size_t workspace_bytes(int64_t rows, int64_t cols);
+hipError_t launch_quantize(const QuantArgs& a, hipStream_t s);
+hipError_t launch_stats(const StatsArgs& a, hipStream_t s);
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+
+}  // namespace snip

@@ -1,0 +1,199 @@
+"""ctypes binding of the C-ABI library declared in include/snip.h.
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.  PyTorch
+is used for device memory and for the current stream, nothing else.  There is no fallback: if
+the library has not been built, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsnip_hip.so")
+
+FP8, FP4 = 0, 1
+ROW, COL = 0, 1
+NO_OVERFLOW, OCP_FLOOR = 0, 1
+OUT_BF16, OUT_FP32 = 0, 1
+
+EXPORTS = ("snip_qtensor_code_bytes", "snip_qtensor_scale_bytes", "snip_workspace_bytes",
+           "snip_quantize", "snip_gemm_fwd", "snip_gemm_dgrad", "snip_gemm_wgrad",
+           "snip_quant_error_stats", "snip_status_string")
+
+
+class SnipError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib().snip_status_string(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class _QTensorC(ctypes.Structure):
+    _fields_ = [("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("fmt", ctypes.c_int32)]
+
+
+class _PlanC(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("fwd_x", "fwd_w", "dgrad_dy", "dgrad_w", "wgrad_dy", "wgrad_x")]
+
+
+_handle = None
+
+
+def _lib():
+    global _handle
+    if _handle is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2602_01410_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        lib.snip_qtensor_code_bytes.restype = sz
+        lib.snip_qtensor_code_bytes.argtypes = [i64, i64, ci]
+        lib.snip_qtensor_scale_bytes.restype = sz
+        lib.snip_qtensor_scale_bytes.argtypes = [i64, i64]
+        lib.snip_workspace_bytes.restype = sz
+        lib.snip_workspace_bytes.argtypes = [i64, i64]
+        lib.snip_quantize.restype = ci
+        lib.snip_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, ctypes.POINTER(_QTensorC), vp, vp, sz, vp]
+        for name in ("snip_gemm_fwd", "snip_gemm_dgrad", "snip_gemm_wgrad"):
+            fn = getattr(lib, name)
+            fn.restype = ci
+            fn.argtypes = [ctypes.POINTER(_PlanC), ctypes.POINTER(_QTensorC), ctypes.POINTER(_QTensorC),
+                           vp, i64, ci, vp, sz, vp]
+        lib.snip_quant_error_stats.restype = ci
+        lib.snip_quant_error_stats.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, vp, sz, vp]
+        lib.snip_status_string.restype = ctypes.c_char_p
+        lib.snip_status_string.argtypes = [ci]
+        _handle = lib
+    return _handle
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise SnipError(status, where)
+
+
+@dataclass
+class QTensor:
+    """A quantized matrix in its stored orientation (cols = contraction extent)."""
+    codes: torch.Tensor      # uint8 [rows, cols] (FP8) or [rows, cols // 2] (FP4)
+    scales: torch.Tensor     # uint8 [rows, cols // 32]
+    rows: int
+    cols: int
+    fmt: int
+
+    def c_struct(self) -> _QTensorC:
+        return _QTensorC(self.codes.data_ptr(), self.scales.data_ptr(), self.rows, self.cols, self.fmt)
+
+
+def code_bytes(rows: int, cols: int, fmt: int) -> int:
+    return _lib().snip_qtensor_code_bytes(rows, cols, fmt)
+
+
+def scale_bytes(rows: int, cols: int) -> int:
+    return _lib().snip_qtensor_scale_bytes(rows, cols)
+
+
+def workspace_bytes(rows: int, cols: int) -> int:
+    return _lib().snip_workspace_bytes(rows, cols)
+
+
+def alloc_qtensor(rows: int, cols: int, fmt: int, device="cuda") -> QTensor:
+    cb = cols if fmt == FP8 else cols // 2
+    return QTensor(torch.empty((rows, cb), dtype=torch.uint8, device=device),
+                   torch.empty((rows, cols // 32), dtype=torch.uint8, device=device), rows, cols, fmt)
+
+
+def alloc_workspace(rows: int, cols: int, device="cuda") -> torch.Tensor:
+    return torch.empty(workspace_bytes(rows, cols), dtype=torch.uint8, device=device)
+
+
+def alloc_stats(device="cuda") -> torch.Tensor:
+    """One snip_stats: float64 [3] = (sum_sq, err_sq_fp4, err_sq_fp8)."""
+    return torch.empty(3, dtype=torch.float64, device=device)
+
+
+def make_plan(entry: Sequence[int]) -> _PlanC:
+    return _PlanC(*[int(v) for v in entry])
+
+
+def _src(x: torch.Tensor):
+    if x.dim() != 2 or x.element_size() != 2 or not x.is_cuda:
+        raise ValueError("expected a 2-D CUDA tensor of bf16 (or its uint16/int16 bit patterns)")
+    if x.stride(1) != 1:
+        raise ValueError("rows must be contiguous")
+    return x.data_ptr(), x.shape[0], x.shape[1], x.stride(0)
+
+
+def snip_quantize(x: torch.Tensor, fmt: int, axis: int = ROW, rule: int = NO_OVERFLOW,
+                  out: Optional[QTensor] = None, stats: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None, stream=None) -> QTensor:
+    ptr, rows, cols, ld = _src(x)
+    if out is None:
+        sr, sc = (rows, cols) if axis == ROW else (cols, rows)
+        out = alloc_qtensor(sr, sc, fmt, x.device)
+    if stats is not None and workspace is None:
+        workspace = alloc_workspace(rows, cols, x.device)
+    q = out.c_struct()
+    _check(_lib().snip_quantize(ptr, rows, cols, ld, fmt, axis, rule, ctypes.byref(q),
+                                stats.data_ptr() if stats is not None else None,
+                                workspace.data_ptr() if workspace is not None else None,
+                                workspace.numel() if workspace is not None else 0, _stream(stream)),
+           "snip_quantize")
+    return out
+
+
+def _gemm(fn_name: str, plan, a: QTensor, b: QTensor, out, out_dtype, stream):
+    if not isinstance(plan, _PlanC):
+        plan = make_plan(plan)
+    if out is None:
+        out = torch.empty((a.rows, b.rows), dtype=torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32,
+                          device=a.codes.device)
+    qa, qb = a.c_struct(), b.c_struct()
+    _check(getattr(_lib(), fn_name)(ctypes.byref(plan), ctypes.byref(qa), ctypes.byref(qb), out.data_ptr(),
+                                    out.stride(0), out_dtype, None, 0, _stream(stream)), fn_name)
+    return out
+
+
+def snip_gemm_fwd(plan, xq_row: QTensor, wq_row: QTensor, out=None, out_dtype=OUT_BF16, stream=None):
+    """Y[M,N] from quantize(X, ROW) and quantize(W, ROW)."""
+    return _gemm("snip_gemm_fwd", plan, xq_row, wq_row, out, out_dtype, stream)
+
+
+def snip_gemm_dgrad(plan, dyq_row: QTensor, wq_col: QTensor, out=None, out_dtype=OUT_BF16, stream=None):
+    """dX[M,K] from quantize(dY, ROW) and quantize(W, COL)."""
+    return _gemm("snip_gemm_dgrad", plan, dyq_row, wq_col, out, out_dtype, stream)
+
+
+def snip_gemm_wgrad(plan, dyq_col: QTensor, xq_col: QTensor, out=None, out_dtype=OUT_BF16, stream=None):
+    """dW[N,K] from quantize(dY, COL) and quantize(X, COL)."""
+    return _gemm("snip_gemm_wgrad", plan, dyq_col, xq_col, out, out_dtype, stream)
+
+
+def snip_quant_error_stats(x: torch.Tensor, axis: int = ROW, rule: int = NO_OVERFLOW,
+                           out: Optional[torch.Tensor] = None, per_line: Optional[torch.Tensor] = None,
+                           workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    ptr, rows, cols, ld = _src(x)
+    if out is None:
+        out = alloc_stats(x.device)
+    if workspace is None:
+        workspace = alloc_workspace(rows, cols, x.device)
+    _check(_lib().snip_quant_error_stats(ptr, rows, cols, ld, axis, rule, out.data_ptr(),
+                                         per_line.data_ptr() if per_line is not None else None,
+                                         workspace.data_ptr(), workspace.numel(), _stream(stream)),
+           "snip_quant_error_stats")
+    return out

@@ -1,0 +1,70 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the header declares,
+its size queries are right, and argument validation rejects bad calls before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "snip.h")
+
+
+def lib():
+    from paper_2602_01410_amd import snip
+    if not os.path.exists(snip.LIB_PATH):
+        from paper_2602_01410_amd.build import build_library
+        build_library()
+    return snip
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(snip_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    snip = lib()
+    handle = ctypes.CDLL(snip.LIB_PATH)
+    names = declared_functions()
+    assert set(names) == set(snip.EXPORTS)
+    for n in names:
+        assert hasattr(handle, n), n
+
+
+def test_size_queries():
+    snip = lib()
+    assert snip.code_bytes(10, 64, snip.FP8) == 640
+    assert snip.code_bytes(10, 64, snip.FP4) == 320
+    assert snip.code_bytes(10, 48, snip.FP8) == 0          # not a multiple of 32
+    assert snip.scale_bytes(10, 64) == 20
+    assert snip.workspace_bytes(1024, 4096) >= 8192 * 12
+
+
+def test_validation_rejects_before_launch():
+    snip = lib()
+    L = snip._lib()
+    q = snip._QTensorC(0, 0, 32, 64, 0)
+    # null source
+    assert L.snip_quantize(None, 32, 64, 64, 0, 0, 0, ctypes.byref(q), None, None, 0, None) == 1
+    # a fake but aligned, never dereferenced source pointer: validation only
+    fake = ctypes.c_void_p(0x1000)
+    assert L.snip_quantize(fake, 32, 48, 48, 0, 0, 0, ctypes.byref(q), None, None, 0, None) == 2   # cols % 32
+    assert L.snip_quantize(fake, 32, 64, 64, 7, 0, 0, ctypes.byref(q), None, None, 0, None) == 3   # fmt
+    assert L.snip_quantize(fake, 32, 64, 60, 0, 0, 0, ctypes.byref(q), None, None, 0, None) == 2   # ld < cols
+    assert L.snip_quantize(fake, 32, 64, 68, 0, 0, 0, ctypes.byref(q), None, None, 0, None) == 4   # ld % 8
+    assert L.snip_quantize(fake, 32, 64, 64, 0, 0, 0, ctypes.byref(q), None, None, 0, None) == 1   # null codes
+    assert L.snip_quant_error_stats(fake, 32, 64, 64, 0, 0, fake, None, None, 0, None) == 5        # workspace
+    assert L.snip_quant_error_stats(fake, 31, 64, 64, 1, 0, fake, None, fake, 1 << 30, None) == 2  # rows % 32 (COL)
+    plan = snip.make_plan((0,) * 6)
+    assert L.snip_gemm_fwd(ctypes.byref(plan), None, None, fake, 64, 0, None, 0, None) == 1
+    assert L.snip_status_string(4).decode().startswith("bad alignment")
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    from paper_2602_01410_amd import snip
+    monkeypatch.setattr(snip, "_handle", None)
+    monkeypatch.setattr(snip, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        snip.workspace_bytes(1, 32)

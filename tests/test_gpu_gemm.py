@@ -1,0 +1,125 @@
+"""GPU parity: the three GEMMs against the oracle's fp64 product of the dequantized operands."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_01410_amd import workloads as wl
+
+from gpu_util import host, host_bf16_as_f64, rel_fro, require_gpu, to_dev
+
+pytestmark = pytest.mark.gpu
+TOL_BF16 = 2e-3      # relative Frobenius error, bf16 output (one RNE to bf16 costs ~1.7e-3)
+TOL_F32 = 1e-4       # fp32 output: the matrix core sums the 64 products of one instruction with a
+                     # shared alignment, not as IEEE fp32 adds; measured 1e-5 .. 3e-5
+
+
+def layer_gemms(snip, X, W, dY, entry, out_dtype):
+    """Run quantize + the three GEMMs of one linear on the GPU."""
+    fx, fw, gdy, gw, wdy, wx = entry
+    dX_, dW_ = to_dev(X), to_dev(W)
+    ddY = to_dev(dY)
+    plan = snip.make_plan(entry)
+    y = snip.snip_gemm_fwd(plan, snip.snip_quantize(dX_, fx, snip.ROW), snip.snip_quantize(dW_, fw, snip.ROW),
+                           out_dtype=out_dtype)
+    dx = snip.snip_gemm_dgrad(plan, snip.snip_quantize(ddY, gdy, snip.ROW), snip.snip_quantize(dW_, gw, snip.COL),
+                              out_dtype=out_dtype)
+    dw = snip.snip_gemm_wgrad(plan, snip.snip_quantize(ddY, wdy, snip.COL), snip.snip_quantize(dX_, wx, snip.COL),
+                              out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    return y, dx, dw
+
+
+def oracle_gemms(X, W, dY, entry):
+    fx, fw, gdy, gw, wdy, wx = entry
+    y = oracle.gemm_fwd(oracle.fake_quant(X, fx, oracle.ROW), oracle.fake_quant(W, fw, oracle.ROW))
+    dx = oracle.gemm_dgrad(oracle.fake_quant(dY, gdy, oracle.ROW), oracle.fake_quant(W, gw, oracle.COL))
+    dw = oracle.gemm_wgrad(oracle.fake_quant(dY, wdy, oracle.COL), oracle.fake_quant(X, wx, oracle.COL))
+    return y, dx, dw
+
+
+def as_f64(t):
+    return host_bf16_as_f64(t) if t.dtype == torch.bfloat16 else host(t).astype(np.float64)
+
+
+@pytest.mark.parametrize("entry", [(0,) * 6, (1,) * 6, (0, 1, 1, 0, 0, 1), (1, 0, 0, 1, 1, 0)])
+def test_small_integers_are_exact(entry):
+    """Operands whose quantization is exact and whose products and partial sums need fewer than
+    21 bits (element range 2^3.6, row scales 2^-1..2^1, at most 384 terms): every summation order
+    is exact in fp32, so the output must equal the oracle exactly.  This pins every operand and
+    scale register layout."""
+    snip = require_gpu()
+    rng = np.random.default_rng(40)
+    M, N, K = 160, 224, 384
+    vals = np.array([-6, -4, -3, -2, -1.5, -1, -.5, 0, .5, 1, 1.5, 2, 3, 4, 6.0])
+    def draw(r, c, scale_rows):
+        a = rng.choice(vals, size=(r, c))
+        a *= 2.0 ** rng.integers(-1, 2, size=(r, 1)) if scale_rows else 1.0
+        return wl.f32_to_bf16_bits(a.astype(np.float32))
+    X, W, dY = draw(M, K, True), draw(N, K, True), draw(M, N, True)
+    got = layer_gemms(snip, X, W, dY, entry, snip.OUT_FP32)
+    want = oracle_gemms(X, W, dY, entry)
+    for g, w in zip(got, want):
+        assert np.array_equal(host(g).astype(np.float64), w)
+
+
+@pytest.mark.parametrize("out_dtype,tol", [(0, TOL_BF16), (1, TOL_F32)])
+def test_config1_full(out_dtype, tol):
+    snip = require_gpu()
+    cfg = wl.CONFIGS[1]
+    lay = wl.make_layer(cfg)
+    entry = wl.make_plan(cfg, "fp8")[0]
+    got = layer_gemms(snip, lay.X["x"], lay.W["lin"], lay.dY["lin"], entry, out_dtype)
+    want = oracle_gemms(lay.X["x"], lay.W["lin"], lay.dY["lin"], entry)
+    for g, w in zip(got, want):
+        assert g.shape == w.shape
+        assert rel_fro(as_f64(g), w) <= tol
+
+
+@pytest.mark.parametrize("entry", [(1,) * 6, (0,) * 6, (0, 1, 1, 0, 1, 0)])
+@pytest.mark.parametrize("out_dtype,tol", [(0, TOL_BF16), (1, TOL_F32)])
+def test_ragged_shapes_all_formats(entry, out_dtype, tol):
+    """Tiles with ragged edges in every dimension; contraction extents that are odd multiples
+    of 32 (scale rows not dword aligned, last stage partial)."""
+    snip = require_gpu()
+    rng = np.random.default_rng(41)
+    M, N, K = 352, 416, 608          # all multiples of 32 (each is a contraction extent of one GEMM)
+    X = wl.f32_to_bf16_bits(rng.standard_t(3, size=(M, K)).astype(np.float32))
+    W = wl.f32_to_bf16_bits((rng.standard_normal((N, K)) * 0.02).astype(np.float32))
+    dY = wl.f32_to_bf16_bits((rng.standard_normal((M, N)) * 1e-3).astype(np.float32))
+    got = layer_gemms(snip, X, W, dY, entry, out_dtype)
+    want = oracle_gemms(X, W, dY, entry)
+    for g, w in zip(got, want):
+        assert rel_fro(as_f64(g), w) <= tol
+
+
+def test_strided_output_and_untouched_padding():
+    snip = require_gpu()
+    rng = np.random.default_rng(42)
+    X = wl.f32_to_bf16_bits(rng.standard_normal((96, 256)).astype(np.float32))
+    W = wl.f32_to_bf16_bits(rng.standard_normal((72, 256)).astype(np.float32))
+    xq = snip.snip_quantize(to_dev(X), snip.FP8, snip.ROW)
+    wq = snip.snip_quantize(to_dev(W), snip.FP8, snip.ROW)
+    buf = torch.full((96, 80), 7.0, dtype=torch.float32, device="cuda")
+    snip.snip_gemm_fwd((0,) * 6, xq, wq, out=buf[:, :72], out_dtype=snip.OUT_FP32)
+    torch.cuda.synchronize()
+    want = oracle.gemm_fwd(oracle.fake_quant(X, 0), oracle.fake_quant(W, 0))
+    assert rel_fro(host(buf[:, :72]).astype(np.float64), want) <= TOL_F32
+    assert torch.all(buf[:, 72:] == 7.0)
+
+
+def test_error_codes():
+    snip = require_gpu()
+    xq = snip.alloc_qtensor(64, 128, snip.FP8)
+    wq = snip.alloc_qtensor(64, 256, snip.FP8)
+    with pytest.raises(snip.SnipError) as e:
+        snip.snip_gemm_fwd((0,) * 6, xq, wq)
+    assert e.value.status == 4          # contraction extents differ
+    wq4 = snip.alloc_qtensor(64, 128, snip.FP4)
+    with pytest.raises(snip.SnipError) as e:
+        snip.snip_gemm_fwd((0,) * 6, xq, wq4)
+    assert e.value.status == 3          # operand format differs from the plan
+    x = torch.zeros((32, 48), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(snip.SnipError) as e:
+        snip.snip_quantize(x, snip.FP8, snip.ROW, out=snip.alloc_qtensor(32, 64, snip.FP8))
+    assert e.value.status == 2

@@ -1,0 +1,157 @@
+"""GPU parity: snip_quantize (and its fused statistics) against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_01410_amd import workloads as wl
+
+from gpu_util import host, require_gpu, to_dev
+
+pytestmark = pytest.mark.gpu
+
+FMTS = [oracle.FP8, oracle.FP4]
+AXES = [oracle.ROW, oracle.COL]
+RULES = [oracle.NO_OVERFLOW, oracle.FLOOR]
+
+
+def wide_range_bits(rng, rows, cols):
+    """bf16 data with block maxima spread over many binades, zeros, signed zeros, subnormals
+    and values on rounding ties."""
+    a = rng.standard_normal((rows, cols)) * 2.0 ** rng.integers(-40, 40, size=(rows, cols // 32)).repeat(32, axis=1)
+    a[rng.random((rows, cols)) < 0.05] = 0.0
+    a[rng.random((rows, cols)) < 0.02] = -0.0
+    bits = wl.f32_to_bf16_bits(a.astype(np.float32))
+    sub = rng.random((rows, cols)) < 0.01
+    bits[sub] = rng.integers(0, 0x80, size=int(sub.sum())).astype(np.uint16) | (rng.integers(0, 2, size=int(sub.sum())).astype(np.uint16) << 15)
+    ties = rng.random((rows, cols)) < 0.05
+    tie_vals = rng.choice(np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, 17.0, 19.0, 432.0, 6.0, 448.0], dtype=np.float32),
+                          size=int(ties.sum()))
+    bits[ties] = wl.f32_to_bf16_bits(tie_vals)
+    return bits
+
+
+def check(snip, bits, fmt, axis, rule, ld_pad=0):
+    if ld_pad:
+        wide = np.zeros((bits.shape[0], bits.shape[1] + ld_pad), dtype=np.uint16)
+        wide[:, :bits.shape[1]] = bits
+        x = to_dev(wide)[:, :bits.shape[1]]
+    else:
+        x = to_dev(bits)
+    q = snip.snip_quantize(x, fmt, axis, rule)
+    torch.cuda.synchronize()
+    want_c, want_s = oracle.quantize(bits, fmt, axis, rule)
+    assert np.array_equal(host(q.scales), want_s)
+    assert np.array_equal(host(q.codes), want_c)
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("axis", AXES)
+@pytest.mark.parametrize("rule", RULES)
+def test_wide_range_ragged(fmt, axis, rule):
+    snip = require_gpu()
+    rng = np.random.default_rng(1 + fmt + 2 * axis + 4 * rule)
+    # several 512-element segments / 128-column groups per row plus a ragged tail; five row
+    # blocks for the column kernel (one full unit of four and a partial one)
+    if axis == oracle.ROW:
+        bits = wide_range_bits(rng, 96, 1184)
+    else:
+        bits = np.ascontiguousarray(wide_range_bits(rng, 160, 1216)[:, :1192])
+    check(snip, bits, fmt, axis, rule)
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("axis", AXES)
+def test_col_tail_and_strided_rows(fmt, axis):
+    snip = require_gpu()
+    rng = np.random.default_rng(77)
+    bits = wide_range_bits(rng, 64, 352)[:, :328] if axis == oracle.COL else wide_range_bits(rng, 64, 352)
+    check(snip, np.ascontiguousarray(bits), fmt, axis, oracle.NO_OVERFLOW, ld_pad=24)
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("rule", RULES)
+def test_every_bf16_value(fmt, rule):
+    """All 65536 bit patterns (finite ones) as elements, in blocks led by many different maxima."""
+    snip = require_gpu()
+    allbits = np.arange(65536, dtype=np.uint16)
+    finite = allbits[(allbits & 0x7FFF) < 0x7F80]
+    rng = np.random.default_rng(3)
+    body = rng.permutation(np.tile(finite, 4))
+    body = body[: (len(body) // 2048) * 2048].reshape(-1, 2048)
+    check(snip, body, fmt, oracle.ROW, rule)
+    # sorted: neighbours share a binade, so every value also meets a block maximum close to itself
+    srt = np.sort(finite.astype(np.uint16) & 0x7FFF)
+    srt = srt[: (len(srt) // 1024) * 1024].reshape(-1, 1024)
+    check(snip, srt, fmt, oracle.ROW, rule)
+    check(snip, np.ascontiguousarray(srt[:32, :]), fmt, oracle.COL, rule)
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("axis", AXES)
+def test_nonfinite_and_zero_blocks(fmt, axis):
+    snip = require_gpu()
+    rng = np.random.default_rng(5)
+    bits = wl.f32_to_bf16_bits(rng.standard_normal((64, 128)).astype(np.float32))
+    bits[3, 40] = 0x7F80       # +inf
+    bits[10, 100] = 0xFF80     # -inf
+    bits[20, 5] = 0x7FC0       # NaN
+    bits[33:40, :] = 0
+    bits[35, 7] = 0x8000       # -0 inside an all-zero block
+    check(snip, bits, fmt, axis, oracle.NO_OVERFLOW)
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+def test_config1_tensors_all_axes(fmt):
+    snip = require_gpu()
+    lay = wl.make_layer(wl.CONFIGS[1])
+    for bits in (lay.X["x"], lay.W["lin"], lay.dY["lin"]):
+        for axis in AXES:
+            check(snip, bits, fmt, axis, oracle.NO_OVERFLOW)
+
+
+def test_column_quantize_equals_row_quantize_of_transpose_on_gpu():
+    snip = require_gpu()
+    rng = np.random.default_rng(9)
+    bits = wide_range_bits(rng, 128, 256)
+    a = snip.snip_quantize(to_dev(bits), snip.FP4, snip.COL)
+    b = snip.snip_quantize(to_dev(np.ascontiguousarray(bits.T)), snip.FP4, snip.ROW)
+    torch.cuda.synchronize()
+    assert torch.equal(a.codes, b.codes) and torch.equal(a.scales, b.scales)
+
+
+def test_empty_and_determinism():
+    snip = require_gpu()
+    x = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    q = snip.snip_quantize(x, snip.FP8, snip.ROW)
+    assert q.codes.numel() == 0
+    st = snip.alloc_stats()
+    snip.snip_quantize(x, snip.FP8, snip.ROW, stats=st)
+    torch.cuda.synchronize()
+    assert host(st)[0] == 0.0 and host(st)[2] == 0.0
+    rng = np.random.default_rng(10)
+    xb = to_dev(wide_range_bits(rng, 256, 1024))
+    s1, s2 = snip.alloc_stats(), snip.alloc_stats()
+    q1 = snip.snip_quantize(xb, snip.FP4, snip.COL, stats=s1)
+    q2 = snip.snip_quantize(xb, snip.FP4, snip.COL, stats=s2)
+    torch.cuda.synchronize()
+    assert torch.equal(q1.codes, q2.codes) and torch.equal(q1.scales, q2.scales)
+    assert host(s1).tobytes() == host(s2).tobytes()
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("axis", AXES)
+@pytest.mark.parametrize("rule", RULES)
+def test_fused_stats(fmt, axis, rule):
+    snip = require_gpu()
+    rng = np.random.default_rng(20 + fmt)
+    bits = wl.f32_to_bf16_bits((rng.standard_t(3, size=(320, 1056)) * 0.3).astype(np.float32))
+    st = snip.alloc_stats()
+    snip.snip_quantize(to_dev(bits), fmt, axis, rule, stats=st)
+    torch.cuda.synchronize()
+    got = host(st)
+    want = oracle.stats(bits, axis, rule)
+    assert abs(got[0] - want[0]) <= 1e-5 * want[0]
+    k = 2 if fmt == oracle.FP8 else 1
+    assert abs(got[k] - want[k]) <= 1e-5 * want[k]
+    assert np.isnan(got[3 - k])

@@ -1,0 +1,76 @@
+"""GPU parity: snip_quant_error_stats against the CPU oracle, 1e-5 relative."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_01410_amd import workloads as wl
+
+from gpu_util import host, require_gpu, to_dev
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+def run(snip, bits, axis, rule, per_line=True):
+    x = to_dev(bits)
+    L = bits.shape[0] if axis == oracle.ROW else bits.shape[1]
+    pl = torch.empty((L, 3), dtype=torch.float32, device="cuda") if per_line else None
+    out = snip.snip_quant_error_stats(x, axis, rule, per_line=pl)
+    torch.cuda.synchronize()
+    return host(out), (host(pl) if per_line else None)
+
+
+@pytest.mark.parametrize("axis", [oracle.ROW, oracle.COL])
+@pytest.mark.parametrize("rule", [oracle.NO_OVERFLOW, oracle.FLOOR])
+def test_stats_ragged(axis, rule):
+    snip = require_gpu()
+    rng = np.random.default_rng(30 + axis)
+    rows, cols = (200, 2592) if axis == oracle.ROW else (416, 1336)
+    a = rng.standard_t(3, size=(rows, cols)) * 10.0 ** rng.integers(-3, 3, size=(rows, 1))
+    bits = wl.f32_to_bf16_bits(a.astype(np.float32))
+    got, got_lines = run(snip, bits, axis, rule)
+    want, want_lines = oracle.stats(bits, axis, rule, per_line=True)
+    np.testing.assert_allclose(got, want, rtol=TOL)
+    np.testing.assert_allclose(got_lines, want_lines, rtol=TOL, atol=0)
+
+
+def test_stats_config1_all_tensors():
+    snip = require_gpu()
+    lay = wl.make_layer(wl.CONFIGS[1])
+    for bits in (lay.X["x"], lay.W["lin"], lay.dY["lin"]):
+        for axis in (oracle.ROW, oracle.COL):
+            got, _ = run(snip, bits, axis, oracle.NO_OVERFLOW, per_line=False)
+            np.testing.assert_allclose(got, oracle.stats(bits, axis), rtol=TOL)
+
+
+def test_stats_zero_on_representable_and_match_fused():
+    snip = require_gpu()
+    rng = np.random.default_rng(31)
+    vals = rng.choice(np.array([0, .5, 1, 1.5, 2, 3, 4, 6.0]), size=(64, 256)) * rng.choice([-1.0, 1.0], size=(64, 256))
+    vals *= 2.0 ** rng.integers(-8, 8, size=(64, 1))
+    bits = wl.f32_to_bf16_bits(vals.astype(np.float32))
+    got, _ = run(snip, bits, oracle.ROW, oracle.NO_OVERFLOW, per_line=False)
+    assert got[0] == np.sum(vals ** 2) and got[1] == 0.0 and got[2] == 0.0
+    # fused (quantize + stats) equals stand-alone for the chosen format
+    bits2 = wl.f32_to_bf16_bits(rng.standard_normal((256, 512)).astype(np.float32))
+    alone, _ = run(snip, bits2, oracle.COL, oracle.NO_OVERFLOW, per_line=False)
+    for fmt, k in ((snip.FP4, 1), (snip.FP8, 2)):
+        st = snip.alloc_stats()
+        snip.snip_quantize(to_dev(bits2), fmt, snip.COL, stats=st)
+        torch.cuda.synchronize()
+        f = host(st)
+        np.testing.assert_allclose([f[0], f[k]], [alone[0], alone[k]], rtol=1e-6)
+
+
+def test_stats_deterministic_and_empty():
+    snip = require_gpu()
+    rng = np.random.default_rng(32)
+    bits = wl.f32_to_bf16_bits(rng.standard_normal((512, 1024)).astype(np.float32))
+    a, _ = run(snip, bits, oracle.ROW, oracle.NO_OVERFLOW, per_line=False)
+    b, _ = run(snip, bits, oracle.ROW, oracle.NO_OVERFLOW, per_line=False)
+    assert a.tobytes() == b.tobytes()
+    x = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    out = snip.snip_quant_error_stats(x, snip.ROW)
+    torch.cuda.synchronize()
+    assert host(out).tolist() == [0.0, 0.0, 0.0]
