@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libsnip_hip.so")
-SOURCES = ("api.hip", "quant_kernels.hip", "gemm.hip")
+SOURCES = ("api.hip", "quant_kernels.hip", "gemm.hip", "gemm_fast.hip")
 
 
 def build_library(verbose: bool = False) -> str:

@@ -261,6 +261,7 @@ hipError_t launch_t(const GemmArgs& a, hipStream_t s)
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
 {
     if (a.I == 0 || a.J == 0) return hipSuccess;
+    if (gemm_fast_eligible(a)) return launch_gemm_fast(a, s);
     if (a.fmt_a == kFP8 && a.fmt_b == kFP8) return launch_t<kFP8, kFP8>(a, s);
     if (a.fmt_a == kFP8 && a.fmt_b == kFP4) return launch_t<kFP8, kFP4>(a, s);
     if (a.fmt_a == kFP4 && a.fmt_b == kFP8) return launch_t<kFP4, kFP8>(a, s);

@@ -49,5 +49,7 @@ size_t workspace_bytes(int64_t rows, int64_t cols);
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t s);
 hipError_t launch_stats(const StatsArgs& a, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+bool gemm_fast_eligible(const GemmArgs& a);          // 256x256-tile kernel (gemm_fast.hip)
+hipError_t launch_gemm_fast(const GemmArgs& a, hipStream_t s);
 
 }  // namespace snip

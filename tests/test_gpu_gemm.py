@@ -93,6 +93,45 @@ def test_ragged_shapes_all_formats(entry, out_dtype, tol):
         assert rel_fro(as_f64(g), w) <= tol
 
 
+@pytest.mark.parametrize("fx,fw", [(0, 0), (1, 1), (0, 1), (1, 0)])
+@pytest.mark.parametrize("out_dtype,tol", [(0, TOL_BF16), (1, TOL_F32)])
+def test_large_tile_kernel_ragged_rows(fx, fw, out_dtype, tol):
+    """Contraction extent a multiple of 128 and more than one 128-tile in each direction: the
+    256x256-tile kernel runs; 300 and 520 rows leave ragged tiles in both directions."""
+    snip = require_gpu()
+    rng = np.random.default_rng(43 + fx + 2 * fw)
+    M, N, K = 300, 520, 640
+    X = wl.f32_to_bf16_bits((rng.standard_t(3, size=(M, K)) * 2.0 ** rng.integers(-6, 6, size=(M, 1))).astype(np.float32))
+    W = wl.f32_to_bf16_bits((rng.standard_normal((N, K)) * 0.02).astype(np.float32))
+    y = snip.snip_gemm_fwd((fx, fw, 0, 0, 0, 0), snip.snip_quantize(to_dev(X), fx, snip.ROW),
+                           snip.snip_quantize(to_dev(W), fw, snip.ROW), out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    want = oracle.gemm_fwd(oracle.fake_quant(X, fx, oracle.ROW), oracle.fake_quant(W, fw, oracle.ROW))
+    assert y.shape == want.shape
+    assert rel_fro(as_f64(y), want) <= tol
+    # per-row check: a wrong scale row or a swapped tile would hide in a global norm
+    g = as_f64(y)
+    row_err = np.linalg.norm(g - want, axis=1) / np.linalg.norm(want, axis=1)
+    assert row_err.max() <= 4 * tol
+
+
+@pytest.mark.parametrize("entry", [(0,) * 6, (1,) * 6, (0, 1, 1, 0, 0, 1)])
+def test_large_tile_kernel_exact_integers(entry):
+    """Exactness test again at a size served by the 256x256-tile kernel (several stages of its ring)."""
+    snip = require_gpu()
+    rng = np.random.default_rng(44)
+    M, N, K = 384, 640, 1152
+    vals = np.array([-6, -4, -3, -2, -1.5, -1, -.5, 0, .5, 1, 1.5, 2, 3, 4, 6.0])
+    def draw(r, c):
+        a = rng.choice(vals, size=(r, c)) * 2.0 ** rng.integers(-1, 2, size=(r, 1))
+        return wl.f32_to_bf16_bits(a.astype(np.float32))
+    X, W, dY = draw(M, K), draw(N, K), draw(M, N)
+    got = layer_gemms(snip, X, W, dY, entry, snip.OUT_FP32)
+    want = oracle_gemms(X, W, dY, entry)
+    for g, w in zip(got, want):
+        assert np.array_equal(host(g).astype(np.float64), w)
+
+
 def test_strided_output_and_untouched_padding():
     snip = require_gpu()
     rng = np.random.default_rng(42)
