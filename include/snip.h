@@ -73,10 +73,19 @@ typedef enum { SNIP_OUT_BF16 = 0, SNIP_OUT_FP32 = 1 } snip_out_dtype;
  *   codes : device. FP8: rows*cols bytes, row-major. FP4: rows*cols/2 bytes, row-major, element
  *           2i in the low nibble and 2i+1 in the high nibble of byte i. 16-byte aligned.
  *   scales: device. E8M0 bytes, [rows][cols/32] row-major.
+ *   scales_g4: device or NULL.  A second copy of the same scale bytes, grouped for the GEMMs:
+ *           [ceil(cols/128)][rows_pad][4], i.e. the four scales of 128 consecutive contraction
+ *           elements of a row in one dword, rows contiguous; rows_pad = rows rounded up to a
+ *           multiple of 256 (dwords of rows >= `rows`, and bytes of blocks >= cols/32, are
+ *           unspecified).  4-byte aligned.  snip_quantize fills it when it is not NULL; when both
+ *           operands of a GEMM carry one and cols is a multiple of 128 the GEMM copies its scales
+ *           from it with fully coalesced loads, otherwise it falls back to a slower kernel that
+ *           gathers from `scales`.  Size: snip_qtensor_scale_g4_bytes.
  *   rows, cols: extents of the stored matrix; cols must be a multiple of 32. */
 typedef struct {
     void*    codes;
     uint8_t* scales;
+    uint8_t* scales_g4;
     int64_t  rows, cols;
     int32_t  fmt;            /* snip_fmt */
 } snip_qtensor;
@@ -98,6 +107,7 @@ typedef struct { double sum_sq, err_sq_fp4, err_sq_fp8; } snip_stats;
 /* Bytes of codes / scales for a stored matrix of rows x cols; 0 on a bad argument. */
 size_t snip_qtensor_code_bytes(int64_t rows, int64_t cols, snip_fmt fmt);
 size_t snip_qtensor_scale_bytes(int64_t rows, int64_t cols);
+size_t snip_qtensor_scale_g4_bytes(int64_t rows, int64_t cols);
 
 /* Workspace (device bytes) sufficient for any call below on a source matrix of at most
  * rows x cols, including per-line statistics. */

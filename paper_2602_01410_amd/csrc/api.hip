@@ -32,6 +32,7 @@ snip_status check_qtensor(const snip_qtensor* q)
     if (q->rows < 0 || q->cols <= 0 || q->cols % 32 != 0) return SNIP_ERR_SHAPE;
     if (q->rows >= (int64_t)1 << 31 || q->cols >= (int64_t)1 << 31) return SNIP_ERR_SHAPE;
     if (!aligned16(q->codes)) return SNIP_ERR_LAYOUT;
+    if (q->scales_g4 && (reinterpret_cast<uintptr_t>(q->scales_g4) & 3u)) return SNIP_ERR_LAYOUT;
     return SNIP_OK;
 }
 
@@ -52,8 +53,8 @@ snip_status gemm(const snip_qtensor* a, int fmt_a, const snip_qtensor* b, int fm
     const int64_t align_elems = out_dtype == SNIP_OUT_BF16 ? 8 : 4;
     if (!aligned16(c) || ldc % align_elems != 0) return SNIP_ERR_LAYOUT;
     GemmArgs g;
-    g.a_codes = (const uint8_t*)a->codes; g.a_scales = a->scales; g.fmt_a = fmt_a;
-    g.b_codes = (const uint8_t*)b->codes; g.b_scales = b->scales; g.fmt_b = fmt_b;
+    g.a_codes = (const uint8_t*)a->codes; g.a_scales = a->scales; g.a_scales_g4 = a->scales_g4; g.fmt_a = fmt_a;
+    g.b_codes = (const uint8_t*)b->codes; g.b_scales = b->scales; g.b_scales_g4 = b->scales_g4; g.fmt_b = fmt_b;
     g.I = a->rows; g.J = b->rows; g.R = a->cols;
     g.c = c; g.ldc = ldc; g.out_fp32 = out_dtype == SNIP_OUT_FP32;
     return launch_gemm(g, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
@@ -76,6 +77,12 @@ size_t snip_qtensor_scale_bytes(int64_t rows, int64_t cols)
     return (size_t)rows * (size_t)(cols / 32);
 }
 
+size_t snip_qtensor_scale_g4_bytes(int64_t rows, int64_t cols)
+{
+    if (rows < 0 || cols < 0 || cols % 32 != 0) return 0;
+    return (size_t)g4_pitch(rows) * (size_t)((cols + 127) / 128) * 4;
+}
+
 size_t snip_workspace_bytes(int64_t rows, int64_t cols)
 {
     if (rows < 0 || cols < 0) return 0;
@@ -95,6 +102,7 @@ snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
     const int64_t sr = axis == SNIP_AXIS_ROW ? rows : cols, sc = axis == SNIP_AXIS_ROW ? cols : rows;
     if (out->rows != sr || out->cols != sc) return SNIP_ERR_SHAPE;
     if (!aligned16(out->codes)) return SNIP_ERR_LAYOUT;
+    if (out->scales_g4 && (reinterpret_cast<uintptr_t>(out->scales_g4) & 3u)) return SNIP_ERR_LAYOUT;
     if (stats) {
         if (!workspace || workspace_bytes_ < workspace_bytes(rows, cols)) return SNIP_ERR_WORKSPACE;
         if (!aligned16(workspace)) return SNIP_ERR_LAYOUT;
@@ -102,7 +110,7 @@ snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
     QuantArgs a;
     a.x = (const uint16_t*)x; a.rows = rows; a.cols = cols; a.ld = ld;
     a.fmt = fmt; a.axis = axis; a.rule = rule;
-    a.codes = (uint8_t*)out->codes; a.scales = out->scales;
+    a.codes = (uint8_t*)out->codes; a.scales = out->scales; a.scales_g4 = out->scales_g4;
     a.stats = (double*)stats; a.workspace = workspace;
     return launch_quantize(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
 }

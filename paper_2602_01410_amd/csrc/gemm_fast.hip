@@ -1,15 +1,25 @@
-// Large-tile variant of the block-scaled GEMM for contraction extents that are multiples of 128.
+// Large-tile variant of the block-scaled GEMM, used when both operands carry the grouped scale copy
+// (scales_g4) and the contraction extent is a multiple of the stage length.
 //
-//   workgroup tile 256 x 256, 8 waves (2 x 4), wave tile 128 (A rows) x 64 (B rows)
-//   pipeline stage = 128 contraction elements; operand tiles and their scale dwords are copied
-//   global -> LDS by the load unit itself (global_load_lds), never through VGPRs; a ring of
-//   2-4 stage buffers keeps up to 3 stages in flight; one barrier per stage
-//   LDS rows are unpadded; the 16-byte chunks of a row are XOR-swizzled (on the global-address
-//   side of the copy) so that the 16 lanes served together by a ds_read_b128 hit 16 different
-//   bank groups
+//   workgroup tile 256 x 256, 8 waves (2 x 4), wave tile 128 (A rows) x 64 (B rows), fp32
+//   accumulators in registers (128 per lane).
+//   A pipeline stage is 128 code bytes of every tile row for an FP8 operand and for FP4 x FP4
+//   (256 contraction elements there), so every 128-byte line that is fetched is used whole.
+//   Codes and scale dwords go global -> LDS through the load unit (global_load_lds), never through
+//   VGPRs; a ring of 2 (3 for mixed formats) stage buffers; one barrier per stage.
+//   LDS rows are unpadded; the 16-byte chunks of a row are XOR-swizzled on the global-address side
+//   of the copy so that the 16 lanes served together by a ds_read_b128 hit 16 different bank groups.
+//   The result tile leaves through LDS as well: each wave transposes its 128 x 64 block so that the
+//   global stores are 16 bytes per lane and 128 contiguous bytes per row.
+//
+// The bound that shapes this kernel is L2 -> LDS bandwidth, not the matrix cores: a 256 x 256 tile
+// needs 64 KB per stage, and the 256 CUs together draw about 20 TB/s from L2 at the FP4 MFMA peak.
 //
 // See gemm.hip for the register layout of v_mfma_scale_f32_32x32x64_f8f6f4.
 #include "snip_internal.h"
+#ifndef SNIP_EXP
+#define SNIP_EXP 0
+#endif
 
 namespace snip {
 namespace {
@@ -24,20 +34,44 @@ constexpr int NWAVE = 8, NT = NWAVE * 64;
 constexpr int WTM = 128, WTN = 64;      // wave tile
 constexpr int MB = WTM / 32, NB = WTN / 32;
 
-#define SNIP_GLDS16(gp, lp) __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gp), (__attribute__((address_space(3))) void*)(lp), 16, 0, 0)
-#define SNIP_GLDS4(gp, lp) __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gp), (__attribute__((address_space(3))) void*)(lp), 4, 0, 0)
+// Global -> LDS copy issued by the load unit: lane i's 16 (or 4) bytes land at lds + 16*i (4*i); `lds` is
+// wave-uniform and travels in M0.  Written as inline assembly on purpose: the compiler then keeps no
+// scoreboard entry for these copies and never adds its own (conservative, count-zero) wait in front of LDS
+// reads; completion is enforced by the explicit SNIP_WAIT_VM + barrier of the pipeline below.  The "memory"
+// clobber tells the compiler that LDS contents change here.
+__device__ __forceinline__ unsigned lds_addr(const void* p)
+{
+    return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+__device__ __forceinline__ void glds16(const void* g, unsigned lds)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds) : "memory", "m0");
+}
+__device__ __forceinline__ void glds4(const void* g, unsigned lds)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(g), "s"(lds) : "memory", "m0");
+}
 // s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding: vmcnt[3:0], expcnt[6:4], lgkmcnt[11:8], vmcnt[5:4] in [15:14])
 #define SNIP_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
 
 template <int FA, int FB> struct FCfg {
-    static constexpr int KE = 128;                               // contraction elements per stage
-    static constexpr int SBA = FA == kFP8 ? 128 : 64;            // code bytes per row per stage
-    static constexpr int SBB = FB == kFP8 ? 128 : 64;
-    static constexpr int NST = (SBA + SBB == 128) ? 4 : (SBA + SBB == 192 ? 3 : 2);
-    static constexpr int LA = TM * SBA / 1024 / NWAVE;           // 16-byte copy instructions per wave per stage
-    static constexpr int LB = TN * SBB / 1024 / NWAVE;
-    static constexpr int L = LA + LB + 1;                        // + one scale dword
+    static constexpr bool BOTH4 = FA == kFP4 && FB == kFP4;
+    static constexpr int KE = BOTH4 ? 256 : 128;                 // contraction elements per stage
+    static constexpr int SBA = FA == kFP8 ? KE : KE / 2;         // code bytes per row per stage (128, or 64 for FP4 next to FP8)
+    static constexpr int SBB = FB == kFP8 ? KE : KE / 2;
+    static constexpr int KS = KE / 64;                           // MFMA steps per stage
+    static constexpr int NG = KE / 128;                          // scale dwords (groups of 4 blocks) per row per stage
+    static constexpr int NST = (SBA + SBB == 256) ? 2 : 3;       // ring slots
     static constexpr int A_BYTES = TM * SBA, B_BYTES = TN * SBB;
+    static constexpr int S_BYTES = (TM + TN) * NG * 4;           // scale dwords of one stage
+    static constexpr int SLOT = A_BYTES + B_BYTES + S_BYTES;
+    static constexpr int LDS_BYTES = NST * SLOT;
+    static constexpr int LA = A_BYTES / 1024 / NWAVE;            // 16-byte copy instructions per wave per stage
+    static constexpr int LB = B_BYTES / 1024 / NWAVE;
+    static constexpr int LS = S_BYTES / 256 / NWAVE;             // 4-byte copy instructions per wave per stage
+    static constexpr int L = LA + LB + LS;
+    static_assert(LDS_BYTES >= NWAVE * 16384, "the epilogue needs 16 KB of LDS per wave");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
 // Swizzle: chunk position p of `row` holds logical chunk p ^ f(row); f makes the 16/CPR rows that share
@@ -48,7 +82,22 @@ template <int SB> __device__ __forceinline__ int swz(int row)
     return (row / (16 / CPR)) % CPR;
 }
 
-template <int F, int SB>
+// Chunk offsets (bytes inside a row block) a lane reads for MFMA step ks: FP8 two 16-byte chunks
+// (bytes [16g,16g+16) and [32+16g, ...) of the step's 64-byte slab), FP4 one (bytes [16g, 16g+16) of
+// the step's 32-byte slab).
+template <int F, int SB, int KS>
+__device__ __forceinline__ void frag_offsets(int r32, int g, int* off)
+{
+    const int f = swz<SB>(r32);          // row-block bases are multiples of 32 rows: f depends on r32 only
+    constexpr int NC = F == kFP8 ? 2 * KS : KS;
+#pragma unroll
+    for (int k = 0; k < NC; ++k) {
+        const int c = F == kFP8 ? ((k >> 1) * 4 + (k & 1) * 2 + g) : (k * 2 + g);
+        off[k] = r32 * SB + ((c ^ f) * 16);
+    }
+}
+
+template <int F>
 __device__ __forceinline__ v8i read_frag(const uint8_t* tile, int rowblock_off, const int* off, int ks)
 {
     v8i f = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -65,30 +114,16 @@ __device__ __forceinline__ v8i read_frag(const uint8_t* tile, int rowblock_off, 
 
 template <int FA, int FB, bool OUT_F32>
 __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict__ a_codes,
-                                                       const uint8_t* __restrict__ a_scales,
+                                                       const uint8_t* __restrict__ a_g4,
                                                        const uint8_t* __restrict__ b_codes,
-                                                       const uint8_t* __restrict__ b_scales,
+                                                       const uint8_t* __restrict__ b_g4,
                                                        int I, int J, int R, void* __restrict__ c_out, int64_t ldc,
                                                        int tiles_i, int tiles_j)
 {
     using C = FCfg<FA, FB>;
     constexpr int NST = C::NST;
-    // one object per ring slot, so that the compiler can tell a slot being filled from the slot being read
-    __shared__ __attribute__((aligned(1024))) uint8_t sa0[C::A_BYTES];
-    __shared__ __attribute__((aligned(1024))) uint8_t sa1[C::A_BYTES];
-    __shared__ __attribute__((aligned(1024))) uint8_t sa2[NST > 2 ? C::A_BYTES : 16];
-    __shared__ __attribute__((aligned(1024))) uint8_t sa3[NST > 3 ? C::A_BYTES : 16];
-    __shared__ __attribute__((aligned(1024))) uint8_t sb0[C::B_BYTES];
-    __shared__ __attribute__((aligned(1024))) uint8_t sb1[C::B_BYTES];
-    __shared__ __attribute__((aligned(1024))) uint8_t sb2[NST > 2 ? C::B_BYTES : 16];
-    __shared__ __attribute__((aligned(1024))) uint8_t sb3[NST > 3 ? C::B_BYTES : 16];
-    __shared__ __attribute__((aligned(1024))) uint8_t ss0[2048];
-    __shared__ __attribute__((aligned(1024))) uint8_t ss1[2048];
-    __shared__ __attribute__((aligned(1024))) uint8_t ss2[NST > 2 ? 2048 : 16];
-    __shared__ __attribute__((aligned(1024))) uint8_t ss3[NST > 3 ? 2048 : 16];
-    uint8_t* const pa[4] = {sa0, sa1, sa2, sa3};
-    uint8_t* const pb[4] = {sb0, sb1, sb2, sb3};
-    uint8_t* const ps[4] = {ss0, ss1, ss2, ss3};
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[C::LDS_BYTES];
+    // slot layout: [A codes][B codes][A scale dwords: group-major, 256 rows][B scale dwords]
 
     // tile order: XCD-contiguous runs, then bands of 4 tile rows walked column by column
     const int nblk = tiles_i * tiles_j;
@@ -113,61 +148,61 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
 
     const int64_t a_row_bytes = FA == kFP8 ? R : R / 2;
     const int64_t b_row_bytes = FB == kFP8 ? R : R / 2;
-    const int nkb = R / kBlock;
     const int nstage = R / C::KE;
+    const int64_t a_pitch = g4_pitch(I), b_pitch = g4_pitch(J);      // dwords per scale group
 
     // ---- per-lane source addresses of the global->LDS copies (stage 0) ----
     const uint8_t* ga[C::LA];
     const uint8_t* gb[C::LB];
+    const uint8_t* gs[C::LS];
+    int64_t gs_step[C::LS];
 #pragma unroll
     for (int j = 0; j < C::LA; ++j) {
         constexpr int CPR = C::SBA / 16, RPI = 1024 / C::SBA;
         const int row = (wave * C::LA + j) * RPI + lane / CPR;
         const int c = (lane % CPR) ^ swz<C::SBA>(row);
-        const int grow = min(i0 + row, I - 1);
-        ga[j] = a_codes + (int64_t)grow * a_row_bytes + c * 16;
+        ga[j] = a_codes + (int64_t)min(i0 + row, I - 1) * a_row_bytes + c * 16;     // rows past the end re-read the last row
     }
 #pragma unroll
     for (int j = 0; j < C::LB; ++j) {
         constexpr int CPR = C::SBB / 16, RPI = 1024 / C::SBB;
         const int row = (wave * C::LB + j) * RPI + lane / CPR;
         const int c = (lane % CPR) ^ swz<C::SBB>(row);
-        const int grow = min(j0 + row, J - 1);
-        gb[j] = b_codes + (int64_t)grow * b_row_bytes + c * 16;
+        gb[j] = b_codes + (int64_t)min(j0 + row, J - 1) * b_row_bytes + c * 16;
     }
-    const uint8_t* gs;
-    {
-        const int t = threadIdx.x;
-        gs = t < TM ? a_scales + (int64_t)min(i0 + t, I - 1) * nkb : b_scales + (int64_t)min(j0 + t - TM, J - 1) * nkb;
+#pragma unroll
+    for (int j = 0; j < C::LS; ++j) {
+        // copy q of a stage: operand, scale group inside the stage, quarter of the 256 tile rows
+        const int q = wave * C::LS + j;
+        const int opnd = q / (4 * C::NG), grp = (q % (4 * C::NG)) / 4, quarter = q % 4;
+        const uint8_t* base = opnd == 0 ? a_g4 : b_g4;
+        const int64_t pitch = opnd == 0 ? a_pitch : b_pitch;
+        const int row0 = opnd == 0 ? i0 : j0;                 // the padded pitch covers whole tiles
+        gs[j] = base + ((int64_t)grp * pitch + row0 + quarter * 64 + lane) * 4;
+        gs_step[j] = (int64_t)C::NG * pitch * 4;
     }
+    const unsigned lds0 = lds_addr(lds);
 
     auto issue = [&](int stage, int slot) {
-        const int st = min(stage, nstage - 1);      // past the end: refill with the last stage (keeps the count of
-                                                    // outstanding copies uniform; the data is never read)
+        if (SNIP_EXP == 5) return;
+        const int st = min(stage, nstage - 1);   // past the end (3-slot ring only): refill with the last stage so that
+                                                 // the count of outstanding copies stays uniform; never read
+        const unsigned base = lds0 + slot * C::SLOT;
 #pragma unroll
-        for (int j = 0; j < C::LA; ++j) SNIP_GLDS16(ga[j] + (int64_t)st * C::SBA, pa[slot] + (wave * C::LA + j) * 1024);
+        for (int j = 0; j < C::LA; ++j) glds16(ga[j] + (int64_t)st * C::SBA, base + (wave * C::LA + j) * 1024);
 #pragma unroll
-        for (int j = 0; j < C::LB; ++j) SNIP_GLDS16(gb[j] + (int64_t)st * C::SBB, pb[slot] + (wave * C::LB + j) * 1024);
-        SNIP_GLDS4(gs + st * 4, ps[slot] + wave * 256);
+        for (int j = 0; j < C::LB; ++j) glds16(gb[j] + (int64_t)st * C::SBB, base + C::A_BYTES + (wave * C::LB + j) * 1024);
+#pragma unroll
+        for (int j = 0; j < C::LS; ++j) glds4(gs[j] + st * gs_step[j], base + C::A_BYTES + C::B_BYTES + (wave * C::LS + j) * 256);
     };
 
     // ---- per-lane LDS read offsets ----
-    constexpr int NCA = FA == kFP8 ? 4 : 2, NCB = FB == kFP8 ? 4 : 2;   // chunk reads per stage per row block
+    constexpr int NCA = FA == kFP8 ? 2 * C::KS : C::KS, NCB = FB == kFP8 ? 2 * C::KS : C::KS;
     int offa[NCA], offb[NCB];
-    {
-        const int fa = swz<C::SBA>(r32), fb = swz<C::SBB>(r32);        // row-block bases are multiples of 32: f depends on r32 only
-#pragma unroll
-        for (int k = 0; k < NCA; ++k) {
-            const int c = FA == kFP8 ? ((k >> 1) * 4 + (k & 1) * 2 + g) : (k * 2 + g);
-            offa[k] = r32 * C::SBA + ((c ^ fa) * 16);
-        }
-#pragma unroll
-        for (int k = 0; k < NCB; ++k) {
-            const int c = FB == kFP8 ? ((k >> 1) * 4 + (k & 1) * 2 + g) : (k * 2 + g);
-            offb[k] = r32 * C::SBB + ((c ^ fb) * 16);
-        }
-    }
-    const int sca_off = (wm * WTM + r32) * 4, scb_off = (TM + wn * WTN + r32) * 4;
+    frag_offsets<FA, C::SBA, C::KS>(r32, g, offa);
+    frag_offsets<FB, C::SBB, C::KS>(r32, g, offb);
+    const int sca_off = C::A_BYTES + C::B_BYTES + (wm * WTM + r32) * 4;
+    const int scb_off = C::A_BYTES + C::B_BYTES + TM * C::NG * 4 + (wn * WTN + r32) * 4;
 
     v16f acc[MB][NB];
 #pragma unroll
@@ -178,34 +213,48 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
             for (int k = 0; k < 16; ++k) acc[a][b][k] = 0.f;
 
     auto compute = [&](int slot) {
-        const uint8_t* ta = pa[slot] + wm * WTM * C::SBA;
-        const uint8_t* tb = pb[slot] + wn * WTN * C::SBB;
-        unsigned sa[MB], sb[NB];
+        const uint8_t* base = lds + slot * C::SLOT;
+        const uint8_t* ta = base + wm * WTM * C::SBA;
+        const uint8_t* tb = base + C::A_BYTES + wn * WTN * C::SBB;
+        unsigned sa[C::NG][MB], sb[C::NG][NB];
 #pragma unroll
-        for (int m = 0; m < MB; ++m) sa[m] = *reinterpret_cast<const unsigned*>(ps[slot] + sca_off + m * 128) >> (8 * g);
+        for (int q = 0; q < C::NG; ++q) {
 #pragma unroll
-        for (int n = 0; n < NB; ++n) sb[n] = *reinterpret_cast<const unsigned*>(ps[slot] + scb_off + n * 128) >> (8 * g);
+            for (int m = 0; m < MB; ++m) sa[q][m] = *reinterpret_cast<const unsigned*>(base + sca_off + q * TM * 4 + m * 128) >> (8 * g);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            v8i fa[MB], fb[NB];
+            for (int n = 0; n < NB; ++n) sb[q][n] = *reinterpret_cast<const unsigned*>(base + scb_off + q * TN * 4 + n * 128) >> (8 * g);
+        }
+        v8i fa[2][MB], fb[2][NB];
 #pragma unroll
-            for (int m = 0; m < MB; ++m) fa[m] = read_frag<FA, C::SBA>(ta, m * 32 * C::SBA, offa, ks);
+        for (int m = 0; m < MB; ++m) fa[0][m] = read_frag<FA>(ta, m * 32 * C::SBA, offa, 0);
 #pragma unroll
-            for (int n = 0; n < NB; ++n) fb[n] = read_frag<FB, C::SBB>(tb, n * 32 * C::SBB, offb, ks);
-            constexpr int ca = FB == kFP8 ? 0 : 4, cb = FA == kFP8 ? 0 : 4;
+        for (int n = 0; n < NB; ++n) fb[0][n] = read_frag<FB>(tb, n * 32 * C::SBB, offb, 0);
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < C::KS) {
+#pragma unroll
+                for (int m = 0; m < MB; ++m) fa[nxt][m] = read_frag<FA>(ta, m * 32 * C::SBA, offa, ks + 1);
+#pragma unroll
+                for (int n = 0; n < NB; ++n) fb[nxt][n] = read_frag<FB>(tb, n * 32 * C::SBB, offb, ks + 1);
+            }
+            constexpr int ca = FB == kFP8 ? 0 : 4, cb = FA == kFP8 ? 0 : 4;   // first MFMA operand = B tile, second = A tile
+            const int q = ks >> 1;
 #pragma unroll
             for (int m = 0; m < MB; ++m)
 #pragma unroll
                 for (int n = 0; n < NB; ++n) {
-                    if (ks == 0)
-                        acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[n], fa[m], acc[m][n], ca, cb, 0, (int)sb[n], 0, (int)sa[m]);
+                    if (SNIP_EXP == 2) { acc[m][n][0] += __int_as_float(fb[cur][n][0] ^ fa[cur][m][1]); continue; }
+                    if ((ks & 1) == 0)
+                        acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[cur][n], fa[cur][m], acc[m][n], ca, cb, 0, (int)sb[q][n], 0, (int)sa[q][m]);
                     else
-                        acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[n], fa[m], acc[m][n], ca, cb, 2, (int)sb[n], 2, (int)sa[m]);
+                        acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[cur][n], fa[cur][m], acc[m][n], ca, cb, 2, (int)sb[q][n], 2, (int)sa[q][m]);
                 }
         }
     };
 
-    // ---- pipeline ----
+    // ---- pipeline: iteration s waits for stage s, lets everyone see it, refills the slot freed one
+    //      iteration ago with stage s + NST - 1, and computes ----
 #pragma unroll
     for (int st = 0; st < NST - 1; ++st) issue(st, st);
     for (int s0 = 0; s0 < nstage; s0 += NST) {
@@ -213,45 +262,78 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
         for (int u = 0; u < NST; ++u) {
             const int s = s0 + u;
             if (s < nstage) {
-                SNIP_WAIT_VM((NST - 2) * C::L);
+                if (SNIP_EXP != 5) SNIP_WAIT_VM((NST - 2) * C::L);
                 __builtin_amdgcn_s_barrier();
-                issue(s + NST - 1, (u + NST - 1) % NST);
+                if (NST > 2 || s + 1 < nstage) issue(s + NST - 1, (u + NST - 1) % NST);
                 compute(u);
             }
         }
     }
-    SNIP_WAIT_VM(0);            // no copy may still be in flight when the LDS is handed to another workgroup
+    SNIP_WAIT_VM(0);            // no copy may still be in flight when the LDS is reused below or handed to another workgroup
     __builtin_amdgcn_s_barrier();
+    if (SNIP_EXP == 1 && I > 1) return;
 
-    // ---- epilogue: lane owns row i; register quad q owns columns 8q + 4g .. +3 of each 32-wide block ----
+    // ---- epilogue: every wave transposes its 128 x 64 block through its own 16 KB of LDS ----
+    // In registers, lane (r32, g) of block (m, n) holds C[32m + r32][32n + 8q + 4g + t] in acc[m][n][4q + t].
+    // In LDS a row is ROWB bytes of 16-byte chunks, chunk c of row r stored at position c ^ f(r).
+    {
+        constexpr int ESZ = OUT_F32 ? 4 : 2;
+        constexpr int ROWB = WTN * ESZ;                  // 128 or 256 bytes per row
+        constexpr int CPR = ROWB / 16;                   // 8 or 16 chunks per row
+        constexpr int ROWS_PER_PASS = 16384 / ROWB;      // 128 or 64 rows fit the wave's region
+        constexpr int MB_PER_PASS = ROWS_PER_PASS / 32;
+        uint8_t* reg = lds + wave * 16384;
 #pragma unroll
-    for (int m = 0; m < MB; ++m) {
-        const int i = i0 + wm * WTM + m * 32 + r32;
-        if (i >= I) continue;
+        for (int pass = 0; pass < MB / MB_PER_PASS; ++pass) {
 #pragma unroll
-        for (int n = 0; n < NB; ++n)
+            for (int mm = 0; mm < MB_PER_PASS; ++mm) {
+                const int m = pass * MB_PER_PASS + mm;
+                const int row = mm * 32 + r32;
+                const int f = OUT_F32 ? (row & (CPR - 1)) : ((row >> 1) & (CPR - 1));
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int j = j0 + wn * WTN + n * 32 + 8 * q + 4 * g;
-                const float v0 = acc[m][n][4 * q + 0], v1 = acc[m][n][4 * q + 1];
-                const float v2 = acc[m][n][4 * q + 2], v3 = acc[m][n][4 * q + 3];
-                if (OUT_F32) {
-                    float* p = reinterpret_cast<float*>(c_out) + (int64_t)i * ldc + j;
-                    if (j + 3 < J) *reinterpret_cast<float4*>(p) = make_float4(v0, v1, v2, v3);
-                    else { if (j < J) p[0] = v0; if (j + 1 < J) p[1] = v1; if (j + 2 < J) p[2] = v2; }
-                } else {
-                    __bf16* p = reinterpret_cast<__bf16*>(c_out) + (int64_t)i * ldc + j;
-                    if (j + 3 < J) {
-                        const float2_t lo = {v0, v1}, hi = {v2, v3};
-                        const bf16x2 blo = __builtin_convertvector(lo, bf16x2), bhi = __builtin_convertvector(hi, bf16x2);
-                        *reinterpret_cast<uint2*>(p) = make_uint2(__builtin_bit_cast(unsigned, blo), __builtin_bit_cast(unsigned, bhi));
+                for (int n = 0; n < NB; ++n)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float v0 = acc[m][n][4 * q + 0], v1 = acc[m][n][4 * q + 1];
+                        const float v2 = acc[m][n][4 * q + 2], v3 = acc[m][n][4 * q + 3];
+                        if (OUT_F32) {
+                            const int c = n * 8 + q * 2 + g;             // 4 floats = one chunk
+                            *reinterpret_cast<float4*>(reg + row * ROWB + ((c ^ f) * 16)) = make_float4(v0, v1, v2, v3);
+                        } else {
+                            const int c = n * 4 + q;                     // 4 bf16 = half a chunk
+                            const float2_t lo = {v0, v1}, hi = {v2, v3};
+                            const bf16x2 blo = __builtin_convertvector(lo, bf16x2), bhi = __builtin_convertvector(hi, bf16x2);
+                            *reinterpret_cast<uint2*>(reg + row * ROWB + ((c ^ f) * 16) + 8 * g) =
+                                make_uint2(__builtin_bit_cast(unsigned, blo), __builtin_bit_cast(unsigned, bhi));
+                        }
+                    }
+            }
+            // read back row-contiguous: 64 lanes cover 64 / CPR rows per instruction
+            constexpr int RPI = 64 / CPR;
+#pragma unroll
+            for (int it = 0; it < ROWS_PER_PASS / RPI; ++it) {
+                const int row = it * RPI + lane / CPR;
+                const int c = lane % CPR;
+                const int f = OUT_F32 ? (row & (CPR - 1)) : ((row >> 1) & (CPR - 1));
+                const uint4 v = *reinterpret_cast<const uint4*>(reg + row * ROWB + ((c ^ f) * 16));
+                const int i = i0 + wm * WTM + pass * ROWS_PER_PASS + row;
+                const int j = j0 + wn * WTN + c * (16 / ESZ);
+                if (i < I) {
+                    uint8_t* p = reinterpret_cast<uint8_t*>(c_out) + ((int64_t)i * ldc + j) * ESZ;
+                    if (j + 16 / ESZ <= J) {
+                        *reinterpret_cast<uint4*>(p) = v;
                     } else {
-                        if (j < J) p[0] = (__bf16)v0;
-                        if (j + 1 < J) p[1] = (__bf16)v1;
-                        if (j + 2 < J) p[2] = (__bf16)v2;
+                        const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                        for (int e = 0; e < 16 / ESZ; ++e)
+                            if (j + e < J) {
+                                if (OUT_F32) reinterpret_cast<unsigned*>(p)[e] = w[e];
+                                else reinterpret_cast<uint16_t*>(p)[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                            }
                     }
                 }
             }
+        }
     }
 }
 
@@ -261,10 +343,10 @@ hipError_t launch_fast_t(const GemmArgs& a, hipStream_t s)
     const int ti = (int)((a.I + TM - 1) / TM), tj = (int)((a.J + TN - 1) / TN);
     const dim3 grid((unsigned)(ti * tj)), block(NT);
     if (a.out_fp32)
-        hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, true>), grid, block, 0, s, a.a_codes, a.a_scales, a.b_codes, a.b_scales,
+        hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, true>), grid, block, 0, s, a.a_codes, a.a_scales_g4, a.b_codes, a.b_scales_g4,
                            (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj);
     else
-        hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, false>), grid, block, 0, s, a.a_codes, a.a_scales, a.b_codes, a.b_scales,
+        hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, false>), grid, block, 0, s, a.a_codes, a.a_scales_g4, a.b_codes, a.b_scales_g4,
                            (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj);
     return hipGetLastError();
 }
@@ -273,7 +355,8 @@ hipError_t launch_fast_t(const GemmArgs& a, hipStream_t s)
 
 bool gemm_fast_eligible(const GemmArgs& a)
 {
-    return a.R % 128 == 0 && a.R >= 128 && a.I > 128 && a.J > 128;
+    const int ke = (a.fmt_a == kFP4 && a.fmt_b == kFP4) ? 256 : 128;
+    return a.a_scales_g4 && a.b_scales_g4 && a.R % ke == 0 && a.R >= ke && a.I > 128 && a.J > 128;
 }
 
 hipError_t launch_gemm_fast(const GemmArgs& a, hipStream_t s)

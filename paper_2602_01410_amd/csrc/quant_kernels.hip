@@ -151,37 +151,41 @@ __global__ __launch_bounds__(256) void quant_row_kernel(const uint16_t* __restri
                                                         int cols, int64_t ld,
                                                         uint8_t* __restrict__ codes,
                                                         uint8_t* __restrict__ scales,
+                                                        uint8_t* __restrict__ scales_g4, int64_t kpitch,
                                                         float* __restrict__ partials)
 {
+    // unit = (group of 4 consecutive rows, 512-element segment); the wave's four loads in flight
+    // are the four rows, so that the block-major scale copy gets one dword (4 rows) per block.
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     const int nwaves = gridDim.x * kWavesPerBlock;
     const int spr = (cols + kSeg - 1) / kSeg;
-    const int units = rows * spr;
+    const int units = ((rows + kUnroll - 1) / kUnroll) * spr;
     const int nblk = cols / kBlock;
     float s0 = 0.f, se = 0.f;
 
-    for (int u0 = wave * kUnroll; u0 < units; u0 += nwaves * kUnroll) {
+    for (int u = wave; u < units; u += nwaves) {
+        const int rg = u / spr;
+        const int col = (u - rg * spr) * kSeg + lane * 8;
         uint4 v[kUnroll];
-        int row[kUnroll], col[kUnroll];
         bool act[kUnroll];
 #pragma unroll
         for (int j = 0; j < kUnroll; ++j) {
-            const int u = u0 + j;
-            row[j] = u / spr;
-            col[j] = (u - row[j] * spr) * kSeg + lane * 8;
-            act[j] = u < units && col[j] < cols;
+            const int row = rg * kUnroll + j;
+            act[j] = row < rows && col < cols;
             v[j] = make_uint4(0, 0, 0, 0);
-            if (act[j]) v[j] = *reinterpret_cast<const uint4*>(x + (int64_t)row[j] * ld + col[j]);
+            if (act[j]) v[j] = *reinterpret_cast<const uint4*>(x + (int64_t)row * ld + col);
         }
+        unsigned packed = 0;
 #pragma unroll
         for (int j = 0; j < kUnroll; ++j) {
+            const int row = rg * kUnroll + j;
             const unsigned am = quad_max(amax8(v[j]));
             const unsigned byte = scale_byte<FMT, RULE>(am);
             const float sc = scale_operand(byte);
             const bool bad = byte == 0xFFu;
             const unsigned w[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
-            const int64_t e0 = (int64_t)row[j] * cols + col[j];
+            const int64_t e0 = (int64_t)row * cols + col;
             if (FMT == kFP8) {
                 unsigned c0 = enc8<RULE>(w[0], w[1], sc, byte), c1 = enc8<RULE>(w[2], w[3], sc, byte);
                 if (bad) { c0 = 0; c1 = 0; }
@@ -194,7 +198,24 @@ __global__ __launch_bounds__(256) void quant_row_kernel(const uint16_t* __restri
                 if (STATS) err4(w, c, sc, s0, se, true);
             }
             if (act[j] && (lane & 3) == 0)
-                scales[(int64_t)row[j] * nblk + (col[j] >> 5)] = (uint8_t)byte;
+                scales[(int64_t)row * nblk + (col >> 5)] = (uint8_t)byte;
+            packed |= byte << (8 * j);
+        }
+        // Grouped copy: `packed` holds this block's byte for each of the 4 rows.  Fetch the same
+        // word from the next three quads (the next three blocks of the same 128-element group),
+        // transpose the 4x4 bytes, and let the first lane of every 16 store the four rows' dwords
+        // (16 contiguous bytes).  Rows past the end fall inside the padded pitch.
+        if (scales_g4) {
+            const unsigned p0 = packed;
+            const unsigned p1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)packed, 0x104, 0xF, 0xF, true);   // lane + 4
+            const unsigned p2 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)packed, 0x108, 0xF, 0xF, true);   // lane + 8
+            const unsigned p3 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)packed, 0x10C, 0xF, 0xF, true);   // lane + 12
+            const unsigned a_lo = __builtin_amdgcn_perm(p1, p0, 0x05010400u), a_hi = __builtin_amdgcn_perm(p1, p0, 0x07030602u);
+            const unsigned b_lo = __builtin_amdgcn_perm(p3, p2, 0x05010400u), b_hi = __builtin_amdgcn_perm(p3, p2, 0x07030602u);
+            const uint4 d = make_uint4(__builtin_amdgcn_perm(b_lo, a_lo, 0x05040100u), __builtin_amdgcn_perm(b_lo, a_lo, 0x07060302u),
+                                       __builtin_amdgcn_perm(b_hi, a_hi, 0x05040100u), __builtin_amdgcn_perm(b_hi, a_hi, 0x07060302u));
+            if (col < cols && (lane & 15) == 0)
+                *reinterpret_cast<uint4*>(scales_g4 + ((int64_t)(col >> 7) * kpitch + rg * kUnroll) * 4) = d;
         }
     }
     if (STATS) {
@@ -285,8 +306,8 @@ __device__ __forceinline__ void load_col_block(const uint16_t* __restrict__ p, i
 }
 
 template <int FMT, int RULE, bool STATS>
-__device__ __forceinline__ void quant_one_column(const unsigned* w, unsigned am, uint8_t* __restrict__ dst_codes,
-                                                 uint8_t* __restrict__ dst_scale, bool act, float& s0, float& se)
+__device__ __forceinline__ unsigned quant_one_column(const unsigned* w, unsigned am, uint8_t* __restrict__ dst_codes,
+                                                     uint8_t* __restrict__ dst_scale, bool act, float& s0, float& se)
 {
     const unsigned byte = scale_byte<FMT, RULE>(am);
     const float sc = scale_operand(byte);
@@ -320,6 +341,7 @@ __device__ __forceinline__ void quant_one_column(const unsigned* w, unsigned am,
         }
     }
     if (act) *dst_scale = (uint8_t)byte;
+    return byte;
 }
 
 template <int FMT, int RULE, bool STATS>
@@ -327,6 +349,7 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
                                                         int cols, int64_t ld,
                                                         uint8_t* __restrict__ codes,
                                                         uint8_t* __restrict__ scales,
+                                                        uint8_t* __restrict__ scales_g4, int64_t kpitch,
                                                         float* __restrict__ partials)
 {
     const int lane = threadIdx.x & 63;
@@ -342,6 +365,7 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
         const int c = cg * kColsPerWave + lane * 2;
         const bool act = c < cols;
         const int rb_end = min(nrb, (ru + 1) * kRowBlocksPerUnit);
+        unsigned g4_lo = 0, g4_hi = 0;      // the unit's (up to) four scale bytes of each of the lane's two columns
         for (int rb = ru * kRowBlocksPerUnit; rb < rb_end; ++rb) {
             ColBlock b;
             load_col_block(x + (int64_t)rb * kBlock * ld + c, ld, act, b);
@@ -350,9 +374,15 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
             const int64_t e_hi = e_lo + rows;
             uint8_t* d_lo = codes + (FMT == kFP8 ? e_lo : (e_lo >> 1));
             uint8_t* d_hi = codes + (FMT == kFP8 ? e_hi : (e_hi >> 1));
-            quant_one_column<FMT, RULE, STATS>(b.lo, b.am_lo, d_lo, scales + (int64_t)c * nrb + rb, act, s0, se);
-            quant_one_column<FMT, RULE, STATS>(b.hi, b.am_hi, d_hi, scales + (int64_t)(c + 1) * nrb + rb, act, s0, se);
+            const unsigned y0 = quant_one_column<FMT, RULE, STATS>(b.lo, b.am_lo, d_lo, scales + (int64_t)c * nrb + rb, act, s0, se);
+            const unsigned y1 = quant_one_column<FMT, RULE, STATS>(b.hi, b.am_hi, d_hi, scales + (int64_t)(c + 1) * nrb + rb, act, s0, se);
+            g4_lo |= y0 << (8 * (rb & 3));
+            g4_hi |= y1 << (8 * (rb & 3));
         }
+        // grouped copy: a unit is exactly one group of four blocks; stored row = source column, so
+        // the wave writes 512 consecutive bytes
+        if (scales_g4 && act)
+            *reinterpret_cast<uint2*>(scales_g4 + ((int64_t)ru * kpitch + c) * 4) = make_uint2(g4_lo, g4_hi);
     }
     if (STATS) {
         s0 = wave_sum(s0);
@@ -478,12 +508,15 @@ size_t workspace_bytes(int64_t rows, int64_t cols)
 template <int FMT, int RULE, bool STATS>
 static void launch_q(const QuantArgs& a, float* partials, hipStream_t s)
 {
+    // pitch of the block-major scale copy = padded number of STORED rows
     if (a.axis == 0)
         hipLaunchKernelGGL((quant_row_kernel<FMT, RULE, STATS>), dim3(kStreamBlocks), dim3(256), 0, s,
-                           a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, partials);
+                           a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, a.scales_g4,
+                           g4_pitch(a.rows), partials);
     else
         hipLaunchKernelGGL((quant_col_kernel<FMT, RULE, STATS>), dim3(kStreamBlocks), dim3(256), 0, s,
-                           a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, partials);
+                           a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, a.scales_g4,
+                           g4_pitch(a.cols), partials);
 }
 
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)

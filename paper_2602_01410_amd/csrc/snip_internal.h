@@ -18,6 +18,8 @@ constexpr int kStreamBlocks = 2048;
 constexpr int kWavesPerBlock = 4;
 constexpr int kStreamWaves = kStreamBlocks * kWavesPerBlock;
 constexpr int kMaxColSplits = 64;    // row splits of the column-statistics kernel
+constexpr int kG4Align = 256;    // row pitch (in dwords) of the grouped scale copy is a multiple of this
+__host__ __device__ inline int64_t g4_pitch(int64_t rows) { return (rows + kG4Align - 1) / kG4Align * kG4Align; }
 
 struct QuantArgs {
     const uint16_t* x;
@@ -25,6 +27,7 @@ struct QuantArgs {
     int fmt, axis, rule;
     uint8_t* codes;
     uint8_t* scales;
+    uint8_t* scales_g4;       // [ceil(stored cols / 128)][g4_pitch(stored rows)][4] or nullptr
     double* stats;        // device snip_stats (3 doubles) or nullptr
     void* workspace;
 };
@@ -39,8 +42,8 @@ struct StatsArgs {
 };
 
 struct GemmArgs {
-    const uint8_t* a_codes; const uint8_t* a_scales; int fmt_a;
-    const uint8_t* b_codes; const uint8_t* b_scales; int fmt_b;
+    const uint8_t* a_codes; const uint8_t* a_scales; const uint8_t* a_scales_g4; int fmt_a;
+    const uint8_t* b_codes; const uint8_t* b_scales; const uint8_t* b_scales_g4; int fmt_b;
     int64_t I, J, R;      // C[I][J] = sum_r A[I][r] B[J][r]
     void* c; int64_t ldc; int out_fp32;
 };

@@ -21,7 +21,8 @@ ROW, COL = 0, 1
 NO_OVERFLOW, OCP_FLOOR = 0, 1
 OUT_BF16, OUT_FP32 = 0, 1
 
-EXPORTS = ("snip_qtensor_code_bytes", "snip_qtensor_scale_bytes", "snip_workspace_bytes",
+EXPORTS = ("snip_qtensor_code_bytes", "snip_qtensor_scale_bytes", "snip_qtensor_scale_g4_bytes",
+           "snip_workspace_bytes",
            "snip_quantize", "snip_gemm_fwd", "snip_gemm_dgrad", "snip_gemm_wgrad",
            "snip_quant_error_stats", "snip_status_string")
 
@@ -34,7 +35,7 @@ class SnipError(RuntimeError):
 
 
 class _QTensorC(ctypes.Structure):
-    _fields_ = [("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+    _fields_ = [("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("scales_g4", ctypes.c_void_p),
                 ("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("fmt", ctypes.c_int32)]
 
 
@@ -59,6 +60,8 @@ def _lib():
         lib.snip_qtensor_code_bytes.argtypes = [i64, i64, ci]
         lib.snip_qtensor_scale_bytes.restype = sz
         lib.snip_qtensor_scale_bytes.argtypes = [i64, i64]
+        lib.snip_qtensor_scale_g4_bytes.restype = sz
+        lib.snip_qtensor_scale_g4_bytes.argtypes = [i64, i64]
         lib.snip_workspace_bytes.restype = sz
         lib.snip_workspace_bytes.argtypes = [i64, i64]
         lib.snip_quantize.restype = ci
@@ -95,9 +98,12 @@ class QTensor:
     rows: int
     cols: int
     fmt: int
+    scales_g4: Optional[torch.Tensor] = None   # uint8 [ceil(cols / 128), rows_pad, 4]: grouped copy for the GEMMs
 
     def c_struct(self) -> _QTensorC:
-        return _QTensorC(self.codes.data_ptr(), self.scales.data_ptr(), self.rows, self.cols, self.fmt)
+        return _QTensorC(self.codes.data_ptr(), self.scales.data_ptr(),
+                         self.scales_g4.data_ptr() if self.scales_g4 is not None else None,
+                         self.rows, self.cols, self.fmt)
 
 
 def code_bytes(rows: int, cols: int, fmt: int) -> int:
@@ -108,14 +114,22 @@ def scale_bytes(rows: int, cols: int) -> int:
     return _lib().snip_qtensor_scale_bytes(rows, cols)
 
 
+def scale_g4_bytes(rows: int, cols: int) -> int:
+    return _lib().snip_qtensor_scale_g4_bytes(rows, cols)
+
+
 def workspace_bytes(rows: int, cols: int) -> int:
     return _lib().snip_workspace_bytes(rows, cols)
 
 
-def alloc_qtensor(rows: int, cols: int, fmt: int, device="cuda") -> QTensor:
+def alloc_qtensor(rows: int, cols: int, fmt: int, device="cuda", grouped_scales: bool = True) -> QTensor:
     cb = cols if fmt == FP8 else cols // 2
+    g4 = None
+    if grouped_scales:
+        rows_pad = scale_g4_bytes(rows, cols) // (4 * max(1, (cols + 127) // 128)) if cols else 0
+        g4 = torch.empty(((cols + 127) // 128, rows_pad, 4), dtype=torch.uint8, device=device)
     return QTensor(torch.empty((rows, cb), dtype=torch.uint8, device=device),
-                   torch.empty((rows, cols // 32), dtype=torch.uint8, device=device), rows, cols, fmt)
+                   torch.empty((rows, cols // 32), dtype=torch.uint8, device=device), rows, cols, fmt, g4)
 
 
 def alloc_workspace(rows: int, cols: int, device="cuda") -> torch.Tensor:

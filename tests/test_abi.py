@@ -39,13 +39,15 @@ def test_size_queries():
     assert snip.code_bytes(10, 64, snip.FP4) == 320
     assert snip.code_bytes(10, 48, snip.FP8) == 0          # not a multiple of 32
     assert snip.scale_bytes(10, 64) == 20
+    assert snip.scale_g4_bytes(10, 64) == 256 * 1 * 4          # one group of 4 blocks, rows padded to 256
+    assert snip.scale_g4_bytes(300, 4096) == 512 * 32 * 4
     assert snip.workspace_bytes(1024, 4096) >= 8192 * 12
 
 
 def test_validation_rejects_before_launch():
     snip = lib()
     L = snip._lib()
-    q = snip._QTensorC(0, 0, 32, 64, 0)
+    q = snip._QTensorC(0, 0, 0, 32, 64, 0)
     # null source
     assert L.snip_quantize(None, 32, 64, 64, 0, 0, 0, ctypes.byref(q), None, None, 0, None) == 1
     # a fake but aligned, never dereferenced source pointer: validation only

@@ -43,6 +43,16 @@ def check(snip, bits, fmt, axis, rule, ld_pad=0):
     want_c, want_s = oracle.quantize(bits, fmt, axis, rule)
     assert np.array_equal(host(q.scales), want_s)
     assert np.array_equal(host(q.codes), want_c)
+    # the grouped copy holds the same bytes: [group of 4 blocks][row][4]
+    g4 = host(q.scales_g4)
+    sr, nkb = want_s.shape
+    pad = np.zeros((sr, g4.shape[0] * 4), dtype=np.uint8)
+    pad[:, :nkb] = want_s
+    want_g4 = pad.reshape(sr, g4.shape[0], 4).transpose(1, 0, 2)
+    got_g4 = g4[:, :sr, :].copy()
+    if nkb % 4:                       # bytes of blocks past the end are unspecified
+        got_g4[-1, :, nkb % 4:] = 0
+    assert np.array_equal(got_g4, want_g4)
 
 
 @pytest.mark.parametrize("fmt", FMTS)
