@@ -30,8 +30,12 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
 
 constexpr int TM = 256, TN = 256;       // workgroup tile
-constexpr int NWAVE = 8, NT = NWAVE * 64;
-constexpr int WTM = 128, WTN = 64;      // wave tile
+#ifndef SNIP_WAVES
+#define SNIP_WAVES 8
+#endif
+constexpr int NWAVE = SNIP_WAVES, NT = NWAVE * 64;
+constexpr int WTM = 128, WTN = NWAVE == 8 ? 64 : 128;      // wave tile
+constexpr int WGN = TN / WTN;                              // waves along the B rows (4 or 2)
 constexpr int MB = WTM / 32, NB = WTN / 32;
 
 // Global -> LDS copy issued by the load unit: lane i's 16 (or 4) bytes land at lds + 16*i (4*i); `lds` is
@@ -43,13 +47,14 @@ __device__ __forceinline__ unsigned lds_addr(const void* p)
 {
     return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
 }
-__device__ __forceinline__ void glds16(const void* g, unsigned lds)
+// The source address is a wave-uniform 64-bit base (SGPR pair) plus a 32-bit per-lane byte offset.
+__device__ __forceinline__ void glds16(const uint8_t* base, unsigned lane_off, unsigned lds)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds) : "memory", "m0");
 }
-__device__ __forceinline__ void glds4(const void* g, unsigned lds)
+__device__ __forceinline__ void glds4(const uint8_t* base, unsigned lane_off, unsigned lds)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(g), "s"(lds) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" : : "v"(lane_off), "s"(base), "s"(lds) : "memory", "m0");
 }
 // s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding: vmcnt[3:0], expcnt[6:4], lgkmcnt[11:8], vmcnt[5:4] in [15:14])
 #define SNIP_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
@@ -70,7 +75,7 @@ template <int FA, int FB> struct FCfg {
     static constexpr int LB = B_BYTES / 1024 / NWAVE;
     static constexpr int LS = S_BYTES / 256 / NWAVE;             // 4-byte copy instructions per wave per stage
     static constexpr int L = LA + LB + LS;
-    static_assert(LDS_BYTES >= NWAVE * 16384, "the epilogue needs 16 KB of LDS per wave");
+    static_assert(LDS_BYTES >= NWAVE * (128 * 1024 / NWAVE), "the epilogue needs 128 KB of LDS");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
@@ -143,7 +148,7 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int r32 = lane & 31, g = lane >> 5;
 
     const int64_t a_row_bytes = FA == kFP8 ? R : R / 2;
@@ -151,36 +156,38 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
     const int nstage = R / C::KE;
     const int64_t a_pitch = g4_pitch(I), b_pitch = g4_pitch(J);      // dwords per scale group
 
-    // ---- per-lane source addresses of the global->LDS copies (stage 0) ----
-    const uint8_t* ga[C::LA];
-    const uint8_t* gb[C::LB];
-    const uint8_t* gs[C::LS];
-    int64_t gs_step[C::LS];
+    // ---- source addresses of the global->LDS copies: wave-uniform base + per-lane 32-bit offset ----
+    // Rows past the end of an operand re-read its last row (their products are never stored).
+    unsigned oa[C::LA], ob[C::LB], os[C::LS];
 #pragma unroll
     for (int j = 0; j < C::LA; ++j) {
         constexpr int CPR = C::SBA / 16, RPI = 1024 / C::SBA;
         const int row = (wave * C::LA + j) * RPI + lane / CPR;
         const int c = (lane % CPR) ^ swz<C::SBA>(row);
-        ga[j] = a_codes + (int64_t)min(i0 + row, I - 1) * a_row_bytes + c * 16;     // rows past the end re-read the last row
+        oa[j] = (unsigned)(min(row, I - 1 - i0) * a_row_bytes + c * 16);
     }
 #pragma unroll
     for (int j = 0; j < C::LB; ++j) {
         constexpr int CPR = C::SBB / 16, RPI = 1024 / C::SBB;
         const int row = (wave * C::LB + j) * RPI + lane / CPR;
         const int c = (lane % CPR) ^ swz<C::SBB>(row);
-        gb[j] = b_codes + (int64_t)min(j0 + row, J - 1) * b_row_bytes + c * 16;
+        ob[j] = (unsigned)(min(row, J - 1 - j0) * b_row_bytes + c * 16);
     }
+    // scale copy q of a stage: operand, scale group inside the stage, quarter of the 256 tile rows (the
+    // padded pitch of the grouped copy covers whole tiles)
+    const uint8_t* sbase[C::LS];
+    int64_t sstep[C::LS];
 #pragma unroll
     for (int j = 0; j < C::LS; ++j) {
-        // copy q of a stage: operand, scale group inside the stage, quarter of the 256 tile rows
         const int q = wave * C::LS + j;
         const int opnd = q / (4 * C::NG), grp = (q % (4 * C::NG)) / 4, quarter = q % 4;
-        const uint8_t* base = opnd == 0 ? a_g4 : b_g4;
         const int64_t pitch = opnd == 0 ? a_pitch : b_pitch;
-        const int row0 = opnd == 0 ? i0 : j0;                 // the padded pitch covers whole tiles
-        gs[j] = base + ((int64_t)grp * pitch + row0 + quarter * 64 + lane) * 4;
-        gs_step[j] = (int64_t)C::NG * pitch * 4;
+        sbase[j] = (opnd == 0 ? a_g4 : b_g4) + ((int64_t)grp * pitch + (opnd == 0 ? i0 : j0) + quarter * 64) * 4;
+        sstep[j] = (int64_t)C::NG * pitch * 4;
+        os[j] = lane * 4;
     }
+    const uint8_t* const abase = a_codes + (int64_t)i0 * a_row_bytes;
+    const uint8_t* const bbase = b_codes + (int64_t)j0 * b_row_bytes;
     const unsigned lds0 = lds_addr(lds);
 
     auto issue = [&](int stage, int slot) {
@@ -189,11 +196,11 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                                                  // the count of outstanding copies stays uniform; never read
         const unsigned base = lds0 + slot * C::SLOT;
 #pragma unroll
-        for (int j = 0; j < C::LA; ++j) glds16(ga[j] + (int64_t)st * C::SBA, base + (wave * C::LA + j) * 1024);
+        for (int j = 0; j < C::LA; ++j) glds16(abase + (int64_t)st * C::SBA, oa[j], base + (wave * C::LA + j) * 1024);
 #pragma unroll
-        for (int j = 0; j < C::LB; ++j) glds16(gb[j] + (int64_t)st * C::SBB, base + C::A_BYTES + (wave * C::LB + j) * 1024);
+        for (int j = 0; j < C::LB; ++j) glds16(bbase + (int64_t)st * C::SBB, ob[j], base + C::A_BYTES + (wave * C::LB + j) * 1024);
 #pragma unroll
-        for (int j = 0; j < C::LS; ++j) glds4(gs[j] + st * gs_step[j], base + C::A_BYTES + C::B_BYTES + (wave * C::LS + j) * 256);
+        for (int j = 0; j < C::LS; ++j) glds4(sbase[j] + st * sstep[j], os[j], base + C::A_BYTES + C::B_BYTES + (wave * C::LS + j) * 256);
     };
 
     // ---- per-lane LDS read offsets ----
@@ -254,20 +261,18 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
     };
 
     // ---- pipeline: iteration s waits for stage s, lets everyone see it, refills the slot freed one
-    //      iteration ago with stage s + NST - 1, and computes ----
+    //      iteration ago with stage s + NST - 1, and computes.  One basic block per iteration (the slot
+    //      index is a run-time scalar) so that the accumulators never cross a control-flow join. ----
 #pragma unroll
     for (int st = 0; st < NST - 1; ++st) issue(st, st);
-    for (int s0 = 0; s0 < nstage; s0 += NST) {
-#pragma unroll
-        for (int u = 0; u < NST; ++u) {
-            const int s = s0 + u;
-            if (s < nstage) {
-                if (SNIP_EXP != 5) SNIP_WAIT_VM((NST - 2) * C::L);
-                __builtin_amdgcn_s_barrier();
-                if (NST > 2 || s + 1 < nstage) issue(s + NST - 1, (u + NST - 1) % NST);
-                compute(u);
-            }
-        }
+    int slot = 0;
+    for (int s = 0; s < nstage; ++s) {
+        if (SNIP_EXP != 5) SNIP_WAIT_VM((NST - 2) * C::L);
+        __builtin_amdgcn_s_barrier();
+        const int fill = slot == 0 ? NST - 1 : slot - 1;       // (slot + NST - 1) % NST
+        if (NST > 2 || s + 1 < nstage) issue(s + NST - 1, fill);
+        compute(slot);
+        slot = slot + 1 == NST ? 0 : slot + 1;
     }
     SNIP_WAIT_VM(0);            // no copy may still be in flight when the LDS is reused below or handed to another workgroup
     __builtin_amdgcn_s_barrier();
@@ -280,9 +285,10 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
         constexpr int ESZ = OUT_F32 ? 4 : 2;
         constexpr int ROWB = WTN * ESZ;                  // 128 or 256 bytes per row
         constexpr int CPR = ROWB / 16;                   // 8 or 16 chunks per row
-        constexpr int ROWS_PER_PASS = 16384 / ROWB;      // 128 or 64 rows fit the wave's region
+        constexpr int REGION = 128 * 1024 / NWAVE;       // LDS bytes a wave may use
+        constexpr int ROWS_PER_PASS = REGION / ROWB < WTM ? REGION / ROWB : WTM;
         constexpr int MB_PER_PASS = ROWS_PER_PASS / 32;
-        uint8_t* reg = lds + wave * 16384;
+        uint8_t* reg = lds + wave * REGION;
 #pragma unroll
         for (int pass = 0; pass < MB / MB_PER_PASS; ++pass) {
 #pragma unroll
@@ -356,6 +362,7 @@ hipError_t launch_fast_t(const GemmArgs& a, hipStream_t s)
 bool gemm_fast_eligible(const GemmArgs& a)
 {
     const int ke = (a.fmt_a == kFP4 && a.fmt_b == kFP4) ? 256 : 128;
+    if (a.R > (1 << 22)) return false;      // per-lane source offsets are 32-bit: 256 rows x row bytes must fit
     return a.a_scales_g4 && a.b_scales_g4 && a.R % ke == 0 && a.R >= ke && a.I > 128 && a.J > 128;
 }
 
