@@ -72,7 +72,7 @@ typedef enum { SNIP_OUT_BF16 = 0, SNIP_OUT_FP32 = 1 } snip_out_dtype;
 /* A quantized matrix in its stored orientation: `cols` is the blocked (contraction) extent.
  *   codes : device. FP8: rows*cols bytes, row-major. FP4: rows*cols/2 bytes, row-major, element
  *           2i in the low nibble and 2i+1 in the high nibble of byte i. 16-byte aligned.
- *   scales: device. E8M0 bytes, [rows][cols/32] row-major.
+ *   scales: device. E8M0 bytes, [rows][cols/32] row-major. 4-byte aligned.
  *   scales_g4: device or NULL.  A second copy of the same scale bytes, grouped for the GEMMs:
  *           [ceil(cols/128)][rows_pad][4], i.e. the four scales of 128 consecutive contraction
  *           elements of a row in one dword, rows contiguous; rows_pad = rows rounded up to a

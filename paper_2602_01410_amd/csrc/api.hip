@@ -33,6 +33,7 @@ snip_status check_qtensor(const snip_qtensor* q)
     if (q->rows >= (int64_t)1 << 31 || q->cols >= (int64_t)1 << 31) return SNIP_ERR_SHAPE;
     if (!aligned16(q->codes)) return SNIP_ERR_LAYOUT;
     if (q->scales_g4 && (reinterpret_cast<uintptr_t>(q->scales_g4) & 3u)) return SNIP_ERR_LAYOUT;
+    if (reinterpret_cast<uintptr_t>(q->scales) & 3u) return SNIP_ERR_LAYOUT;
     return SNIP_OK;
 }
 
@@ -103,6 +104,7 @@ snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
     if (out->rows != sr || out->cols != sc) return SNIP_ERR_SHAPE;
     if (!aligned16(out->codes)) return SNIP_ERR_LAYOUT;
     if (out->scales_g4 && (reinterpret_cast<uintptr_t>(out->scales_g4) & 3u)) return SNIP_ERR_LAYOUT;
+    if (reinterpret_cast<uintptr_t>(out->scales) & 3u) return SNIP_ERR_LAYOUT;
     if (stats) {
         if (!workspace || workspace_bytes_ < workspace_bytes(rows, cols)) return SNIP_ERR_WORKSPACE;
         if (!aligned16(workspace)) return SNIP_ERR_LAYOUT;

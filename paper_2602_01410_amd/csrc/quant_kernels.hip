@@ -305,9 +305,12 @@ __device__ __forceinline__ void load_col_block(const uint16_t* __restrict__ p, i
     }
 }
 
+// Codes of one column's block (32 rows) -> the wave's LDS staging area; returns the scale byte.
+// In LDS the wave keeps a [128 stored rows][ROWB bytes] image of its unit's output (ROWB = 128 FP8,
+// 64 FP4 bytes = 128 source rows); 16-byte chunk c of row r sits at position c ^ ((r >> 1) & (CPR-1)).
 template <int FMT, int RULE, bool STATS>
-__device__ __forceinline__ unsigned quant_one_column(const unsigned* w, unsigned am, uint8_t* __restrict__ dst_codes,
-                                                     uint8_t* __restrict__ dst_scale, bool act, float& s0, float& se)
+__device__ __forceinline__ unsigned quant_one_column(const unsigned* w, unsigned am, uint8_t* __restrict__ lds_row,
+                                                     int rb_local, int swz, float& s0, float& se)
 {
     const unsigned byte = scale_byte<FMT, RULE>(am);
     const float sc = scale_operand(byte);
@@ -319,10 +322,8 @@ __device__ __forceinline__ unsigned quant_one_column(const unsigned* w, unsigned
             c[k] = enc8<RULE>(w[2 * k], w[2 * k + 1], sc, byte);
             if (bad) c[k] = 0;
         }
-        if (act) {
-            reinterpret_cast<uint4*>(dst_codes)[0] = make_uint4(c[0], c[1], c[2], c[3]);
-            reinterpret_cast<uint4*>(dst_codes)[1] = make_uint4(c[4], c[5], c[6], c[7]);
-        }
+        *reinterpret_cast<uint4*>(lds_row + (((rb_local * 2 + 0) ^ swz) * 16)) = make_uint4(c[0], c[1], c[2], c[3]);
+        *reinterpret_cast<uint4*>(lds_row + (((rb_local * 2 + 1) ^ swz) * 16)) = make_uint4(c[4], c[5], c[6], c[7]);
         if (STATS) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) err8(w + 4 * k, c[2 * k], c[2 * k + 1], sc, s0, se, true);
@@ -334,13 +335,12 @@ __device__ __forceinline__ unsigned quant_one_column(const unsigned* w, unsigned
             c[k] = enc4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3], sc);
             if (bad) c[k] = 0;
         }
-        if (act) reinterpret_cast<uint4*>(dst_codes)[0] = make_uint4(c[0], c[1], c[2], c[3]);
+        *reinterpret_cast<uint4*>(lds_row + ((rb_local ^ swz) * 16)) = make_uint4(c[0], c[1], c[2], c[3]);
         if (STATS) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) err4(w + 4 * k, c[k], sc, s0, se, true);
         }
     }
-    if (act) *dst_scale = (uint8_t)byte;
     return byte;
 }
 
@@ -352,37 +352,60 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
                                                         uint8_t* __restrict__ scales_g4, int64_t kpitch,
                                                         float* __restrict__ partials)
 {
+    constexpr int ROWB = FMT == kFP8 ? 128 : 64;     // staged output bytes per stored row (128 source rows)
+    constexpr int CPR = ROWB / 16;
+    __shared__ __attribute__((aligned(16))) uint8_t stage[kWavesPerBlock][kColsPerWave * ROWB];
     const int lane = threadIdx.x & 63;
+    uint8_t* const reg = stage[threadIdx.x >> 6];
     const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     const int nwaves = gridDim.x * kWavesPerBlock;
     const int ncg = (cols + kColsPerWave - 1) / kColsPerWave;
     const int nrb = rows / kBlock;
     const int nru = (nrb + kRowBlocksPerUnit - 1) / kRowBlocksPerUnit;
     const int units = ncg * nru;
+    const int64_t out_row_bytes = FMT == kFP8 ? rows : rows / 2;
     float s0 = 0.f, se = 0.f;
     for (int u = wave; u < units; u += nwaves) {
         const int ru = u / ncg, cg = u - ru * ncg;
         const int c = cg * kColsPerWave + lane * 2;
         const bool act = c < cols;
-        const int rb_end = min(nrb, (ru + 1) * kRowBlocksPerUnit);
-        unsigned g4_lo = 0, g4_hi = 0;      // the unit's (up to) four scale bytes of each of the lane's two columns
-        for (int rb = ru * kRowBlocksPerUnit; rb < rb_end; ++rb) {
+        const int rb0 = ru * kRowBlocksPerUnit;
+        const int nb = min(nrb - rb0, kRowBlocksPerUnit);
+        const int swz_lo = lane & (CPR - 1);          // ((2 * lane) >> 1) & (CPR - 1); the odd row shares it
+        unsigned g4_lo = 0, g4_hi = 0;                // the unit's (up to) four scale bytes of the lane's two columns
+        for (int k = 0; k < nb; ++k) {
             ColBlock b;
-            load_col_block(x + (int64_t)rb * kBlock * ld + c, ld, act, b);
-            // stored matrix is [cols][rows]: column c becomes stored row c
-            const int64_t e_lo = (int64_t)c * rows + (int64_t)rb * kBlock;
-            const int64_t e_hi = e_lo + rows;
-            uint8_t* d_lo = codes + (FMT == kFP8 ? e_lo : (e_lo >> 1));
-            uint8_t* d_hi = codes + (FMT == kFP8 ? e_hi : (e_hi >> 1));
-            const unsigned y0 = quant_one_column<FMT, RULE, STATS>(b.lo, b.am_lo, d_lo, scales + (int64_t)c * nrb + rb, act, s0, se);
-            const unsigned y1 = quant_one_column<FMT, RULE, STATS>(b.hi, b.am_hi, d_hi, scales + (int64_t)(c + 1) * nrb + rb, act, s0, se);
-            g4_lo |= y0 << (8 * (rb & 3));
-            g4_hi |= y1 << (8 * (rb & 3));
+            load_col_block(x + (int64_t)(rb0 + k) * kBlock * ld + c, ld, act, b);
+            const unsigned y0 = quant_one_column<FMT, RULE, STATS>(b.lo, b.am_lo, reg + (2 * lane) * ROWB, k, swz_lo, s0, se);
+            const unsigned y1 = quant_one_column<FMT, RULE, STATS>(b.hi, b.am_hi, reg + (2 * lane + 1) * ROWB, k, swz_lo, s0, se);
+            g4_lo |= y0 << (8 * k);
+            g4_hi |= y1 << (8 * k);
         }
-        // grouped copy: a unit is exactly one group of four blocks; stored row = source column, so
-        // the wave writes 512 consecutive bytes
-        if (scales_g4 && act)
-            *reinterpret_cast<uint2*>(scales_g4 + ((int64_t)ru * kpitch + c) * 4) = make_uint2(g4_lo, g4_hi);
+        // Codes: read the staged image back row-contiguous and store 16 bytes per lane, so that every store
+        // instruction writes whole 128-byte (FP8) or 64-byte (FP4) runs of 64 / CPR stored rows.
+#pragma unroll
+        for (int it = 0; it < kColsPerWave * CPR / 64; ++it) {
+            const int idx = it * 64 + lane;
+            const int row = idx / CPR, chunk = idx % CPR;
+            const uint4 v = *reinterpret_cast<const uint4*>(reg + row * ROWB + ((chunk ^ ((row >> 1) & (CPR - 1))) * 16));
+            const int cc = cg * kColsPerWave + row;
+            const int blk = FMT == kFP8 ? chunk >> 1 : chunk;        // row block this chunk belongs to
+            if (cc < cols && blk < nb)
+                *reinterpret_cast<uint4*>(codes + (int64_t)cc * out_row_bytes + (int64_t)ru * ROWB + chunk * 16) = v;
+        }
+        // Scales: stored row = source column.  The unit's four bytes of a column are adjacent in the row-major
+        // array (one dword when the row length allows it) and form exactly one dword of the grouped copy.
+        if (act) {
+            uint8_t* s_lo = scales + (int64_t)c * nrb + rb0;
+            if ((nrb & 3) == 0) {
+                *reinterpret_cast<unsigned*>(s_lo) = g4_lo;
+                *reinterpret_cast<unsigned*>(s_lo + nrb) = g4_hi;
+            } else {
+                for (int k = 0; k < nb; ++k) { s_lo[k] = (uint8_t)(g4_lo >> (8 * k)); s_lo[nrb + k] = (uint8_t)(g4_hi >> (8 * k)); }
+            }
+            if (scales_g4)
+                *reinterpret_cast<uint2*>(scales_g4 + ((int64_t)ru * kpitch + c) * 4) = make_uint2(g4_lo, g4_hi);
+        }
     }
     if (STATS) {
         s0 = wave_sum(s0);
@@ -446,18 +469,31 @@ __global__ __launch_bounds__(256) void stats_col_kernel(const uint16_t* __restri
     }
 }
 
-// Second stage: sum n per-wave partials [n][3] in double, fixed order, one block.
+// Second stage: sum n per-wave partials [n][3] in double, fixed order, one block of 1024 threads.
+// Thread t owns partials 8t .. 8t+7 (and the same window every 8192 partials), read as six float4.
 // mode 0: out = {p0, p1, p2}; mode 1 (fused FP4): out = {p0, p1, NaN}; mode 2 (fused FP8): {p0, NaN, p1}.
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partials, int n,
-                                                              int mode, double* __restrict__ out)
+constexpr int kReduceThreads = 1024;
+__global__ __launch_bounds__(kReduceThreads) void reduce_partials_kernel(const float* __restrict__ partials, int n,
+                                                                         int mode, double* __restrict__ out)
 {
-    __shared__ double sh[3][256];
+    __shared__ double sh[3][kReduceThreads];
     double a[3] = {0.0, 0.0, 0.0};
-    for (int i = threadIdx.x; i < n; i += 256)
-        for (int j = 0; j < 3; ++j) a[j] += (double)partials[i * 3 + j];
+    for (int base = threadIdx.x * 8; base < n; base += kReduceThreads * 8) {
+        if (base + 8 <= n) {
+            const float4* p = reinterpret_cast<const float4*>(partials + (size_t)base * 3);
+            float v[24];
+#pragma unroll
+            for (int k = 0; k < 6; ++k) { const float4 q = p[k]; v[4 * k] = q.x; v[4 * k + 1] = q.y; v[4 * k + 2] = q.z; v[4 * k + 3] = q.w; }
+#pragma unroll
+            for (int k = 0; k < 24; ++k) a[k % 3] += (double)v[k];
+        } else {
+            for (int i = base; i < n; ++i)
+                for (int j = 0; j < 3; ++j) a[j] += (double)partials[(size_t)i * 3 + j];
+        }
+    }
     for (int j = 0; j < 3; ++j) sh[j][threadIdx.x] = a[j];
     __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
+    for (int s = kReduceThreads / 2; s > 0; s >>= 1) {
         if ((int)threadIdx.x < s)
             for (int j = 0; j < 3; ++j) sh[j][threadIdx.x] += sh[j][threadIdx.x + s];
         __syncthreads();
@@ -523,7 +559,7 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
 {
     if (a.rows == 0 || a.cols == 0) {
         if (a.stats) {
-            hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, s,
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(kReduceThreads), 0, s,
                                (const float*)a.workspace, 0, a.fmt == kFP4 ? 1 : 2, a.stats);
         }
         return hipGetLastError();
@@ -545,7 +581,7 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (st) {
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, s,
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(kReduceThreads), 0, s,
                            (const float*)partials, kStreamWaves, a.fmt == kFP4 ? 1 : 2, a.stats);
         e = hipGetLastError();
     }
@@ -556,7 +592,7 @@ hipError_t launch_stats(const StatsArgs& a, hipStream_t s)
 {
     float* partials = (float*)a.workspace;
     if (a.rows == 0 || a.cols == 0) {
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, s, (const float*)partials, 0, 0, a.stats);
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(kReduceThreads), 0, s, (const float*)partials, 0, 0, a.stats);
         return hipGetLastError();
     }
     int npart;
@@ -589,7 +625,7 @@ hipError_t launch_stats(const StatsArgs& a, hipStream_t s)
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, s, (const float*)partials, npart, 0, a.stats);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(kReduceThreads), 0, s, (const float*)partials, npart, 0, a.stats);
     return hipGetLastError();
 }
 
