@@ -22,8 +22,8 @@ import numpy as np
 import torch
 
 PEAK = {"fp4": 10.1e15, "fp8": 5.0e15, "hbm": 8.0e12}
-KERNEL_NAME = {(0, 0): "gemm_kernel<fp8,fp8>", (1, 1): "gemm_kernel<fp4,fp4>",
-               (0, 1): "gemm_kernel<fp8,fp4>", (1, 0): "gemm_kernel<fp4,fp8>"}
+KERNEL_NAME = {(0, 0): "gemm_fast_kernel<fp8,fp8>", (1, 1): "gemm_fast_kernel<fp4,fp4>",
+               (0, 1): "gemm_fast_kernel<fp8,fp4>", (1, 0): "gemm_fast_kernel<fp4,fp8>"}
 
 
 def parse():
