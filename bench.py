@@ -34,6 +34,8 @@ def parse():
     p.add_argument("--config", type=int, default=4, help="workload configuration 1..5 (default: Llama-7B-shaped layer)")
     p.add_argument("--plan", type=str, default=None, help="fp4 | fp8 | mixNN | tensor (default: the config's mixed plan)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--microbench", action="store_true",
+                   help="run the device microbenchmarks (measured MFMA / HBM / L2 rates) and exit")
     return p.parse_args()
 
 
@@ -136,6 +138,10 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.microbench:
+        import subprocess
+        exe = os.path.join(ROOT, "paper_2602_01410_amd", "snip_microbench")
+        sys.exit(subprocess.run([exe]).returncode)
     from paper_2602_01410_amd import snip, workloads as wl
     snip._lib()
     cfg = wl.CONFIGS[args.config]

@@ -7,6 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libsnip_hip.so")
+MICROBENCH = os.path.join(_HERE, "snip_microbench")
 SOURCES = ("api.hip", "quant_kernels.hip", "gemm.hip", "gemm_fast.hip")
 
 
@@ -21,6 +22,15 @@ def build_library(verbose: bool = False) -> str:
         print(res.stderr)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed building libsnip_hip.so")
+    # device microbenchmarks (measured roofline denominators), run by `bench.py --microbench`
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-o", MICROBENCH,
+           os.path.join(CSRC, "microbench.hip")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        print(res.stdout)
+        print(res.stderr)
+        raise RuntimeError("hipcc failed building snip_microbench")
     return LIB
 
 
