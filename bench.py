@@ -22,6 +22,9 @@ import numpy as np
 import torch
 
 PEAK = {"fp4": 10.1e15, "fp8": 5.0e15, "hbm": 8.0e12}
+# L2-miss-side bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated against a copy kernel), measured with
+# rocprofv3 --pmc on this command; see profiles/hbm_traffic_config4_mix50.md.  Keyed by (config, plan, kernel).
+MEASURED_TRAFFIC = {(4, "mix50", "gemm_fast_kernel<fp4,fp4>"): 539.3e6}
 KERNEL_NAME = {(0, 0): "gemm_fast_kernel<fp8,fp8>", (1, 1): "gemm_fast_kernel<fp4,fp4>",
                (0, 1): "gemm_fast_kernel<fp8,fp4>", (1, 0): "gemm_fast_kernel<fp4,fp8>"}
 
@@ -196,7 +199,8 @@ def main():
         "ms_gemm": gemm_sec * 1e3, "ms_quantize": q_sec * 1e3, "ms_stats": s_sec * 1e3,
         "input_generation_s": layer.gen_seconds,
         "roofline": {"bound": "mfma", "kernel": KERNEL_NAME[dom], "achieved": achieved / 1e12, "peak": peak / 1e12,
-                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": MEASURED_TRAFFIC.get((cfg.index, plan_name, KERNEL_NAME[dom])),
                      "launches": dn, "avg_launch_us": dsec / dn * 1e6, "avg_flop_per_launch": dfl / dn},
     }
     if not args.no_cpu_baseline:
