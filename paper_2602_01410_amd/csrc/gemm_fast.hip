@@ -6,7 +6,10 @@
 //   A pipeline stage is 128 code bytes of every tile row for an FP8 operand and for FP4 x FP4
 //   (256 contraction elements there), so every 128-byte line that is fetched is used whole.
 //   Codes and scale dwords go global -> LDS through the load unit (global_load_lds), never through
-//   VGPRs; a ring of 2 (3 for mixed formats) stage buffers; one barrier per stage.
+//   VGPRs; two stage buffers.
+//   The eight waves run a ping-pong schedule: the two waves of a SIMD alternate between reading
+//   their operands of a phase from LDS and issuing that phase's MFMAs, one phase apart, separated by
+//   workgroup barriers, so that the matrix core of every SIMD always has a wave with operands ready.
 //   LDS rows are unpadded; the 16-byte chunks of a row are XOR-swizzled on the global-address side
 //   of the copy so that the 16 lanes served together by a ds_read_b128 hit 16 different bank groups.
 //   The result tile leaves through LDS as well: each wave transposes its 128 x 64 block so that the
@@ -17,9 +20,6 @@
 //
 // See gemm.hip for the register layout of v_mfma_scale_f32_32x32x64_f8f6f4.
 #include "snip_internal.h"
-#ifndef SNIP_EXP
-#define SNIP_EXP 0
-#endif
 
 namespace snip {
 namespace {
@@ -66,11 +66,11 @@ template <int FA, int FB> struct FCfg {
     static constexpr int SBB = FB == kFP8 ? KE : KE / 2;
     static constexpr int KS = KE / 64;                           // MFMA steps per stage
     static constexpr int NG = KE / 128;                          // scale dwords (groups of 4 blocks) per row per stage
-    static constexpr int NST = (SBA + SBB == 256) ? 2 : 3;       // ring slots
+    static constexpr int NST = 2;                                // stage buffers
     static constexpr int A_BYTES = TM * SBA, B_BYTES = TN * SBB;
     static constexpr int S_BYTES = (TM + TN) * NG * 4;           // scale dwords of one stage
     static constexpr int SLOT = A_BYTES + B_BYTES + S_BYTES;
-    static constexpr int LDS_BYTES = NST * SLOT;
+    static constexpr int LDS_BYTES = NST * SLOT > 128 * 1024 ? NST * SLOT : 128 * 1024;   // the epilogue stages 128 KB
     static constexpr int LA = A_BYTES / 1024 / NWAVE;            // 16-byte copy instructions per wave per stage
     static constexpr int LB = B_BYTES / 1024 / NWAVE;
     static constexpr int LS = S_BYTES / 256 / NWAVE;             // 4-byte copy instructions per wave per stage
@@ -126,7 +126,6 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                                                        int tiles_i, int tiles_j)
 {
     using C = FCfg<FA, FB>;
-    constexpr int NST = C::NST;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[C::LDS_BYTES];
     // slot layout: [A codes][B codes][A scale dwords: group-major, 256 rows][B scale dwords]
 
@@ -191,9 +190,7 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
     const unsigned lds0 = lds_addr(lds);
 
     auto issue = [&](int stage, int slot) {
-        if (SNIP_EXP == 5) return;
-        const int st = min(stage, nstage - 1);   // past the end (3-slot ring only): refill with the last stage so that
-                                                 // the count of outstanding copies stays uniform; never read
+        const int st = stage;
         const unsigned base = lds0 + slot * C::SLOT;
 #pragma unroll
         for (int j = 0; j < C::LA; ++j) glds16(abase + (int64_t)st * C::SBA, oa[j], base + (wave * C::LA + j) * 1024);
@@ -219,64 +216,84 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
 #pragma unroll
             for (int k = 0; k < 16; ++k) acc[a][b][k] = 0.f;
 
-    auto compute = [&](int slot) {
-        const uint8_t* base = lds + slot * C::SLOT;
-        const uint8_t* ta = base + wm * WTM * C::SBA;
-        const uint8_t* tb = base + C::A_BYTES + wn * WTN * C::SBB;
-        unsigned sa[C::NG][MB], sb[C::NG][NB];
+    // ---- ping-pong schedule.  The two waves that share a SIMD (wave w and w + 4) belong to different
+    //      groups.  A stage is two phases; in every phase a wave either reads its operands of that phase
+    //      from LDS into registers (R) or issues that phase's MFMAs (M).  Workgroup barriers separate the
+    //      phases and group 1 runs one phase behind group 0, so while one wave of a SIMD feeds the matrix
+    //      core the other one fetches:
+    //          barrier    b0      b1      b2      b3      b4      b5 ...
+    //          group 0        R0(0)   M0(0)   R1(0)   M1(0)   R0(1)   M0(1)
+    //          group 1        -       R0(0)   M0(0)   R1(0)   M1(0)   R0(1)
+    //      Stage s is complete in LDS before b(4s): every wave waits for its own copies before that barrier.
+    //      The slot of stage s-1 is free after b(4s) (group 1 finished R1(s-1) before it). ----
+    {
+        constexpr int KP = C::KS / 2;                      // k-steps per phase
+        v8i fa[KP][MB], fb[KP][NB];
+        unsigned sa[MB], sb[NB];
+        auto R = [&](int slot, int p) {
+            const uint8_t* base = lds + slot * C::SLOT;
+            const uint8_t* ta = base + wm * WTM * C::SBA;
+            const uint8_t* tb = base + C::A_BYTES + wn * WTN * C::SBB;
+            const int q = C::NG == 2 ? p : 0;
 #pragma unroll
-        for (int q = 0; q < C::NG; ++q) {
+            for (int m = 0; m < MB; ++m) sa[m] = *reinterpret_cast<const unsigned*>(base + sca_off + q * TM * 4 + m * 128) >> (8 * g);
 #pragma unroll
-            for (int m = 0; m < MB; ++m) sa[q][m] = *reinterpret_cast<const unsigned*>(base + sca_off + q * TM * 4 + m * 128) >> (8 * g);
+            for (int n = 0; n < NB; ++n) sb[n] = *reinterpret_cast<const unsigned*>(base + scb_off + q * TN * 4 + n * 128) >> (8 * g);
 #pragma unroll
-            for (int n = 0; n < NB; ++n) sb[q][n] = *reinterpret_cast<const unsigned*>(base + scb_off + q * TN * 4 + n * 128) >> (8 * g);
-        }
-        v8i fa[2][MB], fb[2][NB];
+            for (int k = 0; k < KP; ++k) {
 #pragma unroll
-        for (int m = 0; m < MB; ++m) fa[0][m] = read_frag<FA>(ta, m * 32 * C::SBA, offa, 0);
+                for (int m = 0; m < MB; ++m) fa[k][m] = read_frag<FA>(ta, m * 32 * C::SBA, offa, p * KP + k);
 #pragma unroll
-        for (int n = 0; n < NB; ++n) fb[0][n] = read_frag<FB>(tb, n * 32 * C::SBB, offb, 0);
-#pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks + 1 < C::KS) {
-#pragma unroll
-                for (int m = 0; m < MB; ++m) fa[nxt][m] = read_frag<FA>(ta, m * 32 * C::SBA, offa, ks + 1);
-#pragma unroll
-                for (int n = 0; n < NB; ++n) fb[nxt][n] = read_frag<FB>(tb, n * 32 * C::SBB, offb, ks + 1);
+                for (int n = 0; n < NB; ++n) fb[k][n] = read_frag<FB>(tb, n * 32 * C::SBB, offb, p * KP + k);
             }
-            constexpr int ca = FB == kFP8 ? 0 : 4, cb = FA == kFP8 ? 0 : 4;   // first MFMA operand = B tile, second = A tile
-            const int q = ks >> 1;
+        };
+        auto M = [&](int p) {
+            constexpr int ca = FB == kFP8 ? 0 : 4, cb = FA == kFP8 ? 0 : 4;
+            __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-            for (int m = 0; m < MB; ++m)
+            for (int k = 0; k < KP; ++k) {
+                const int ks = p * KP + k;
 #pragma unroll
-                for (int n = 0; n < NB; ++n) {
-                    if (SNIP_EXP == 2) { acc[m][n][0] += __int_as_float(fb[cur][n][0] ^ fa[cur][m][1]); continue; }
-                    if ((ks & 1) == 0)
-                        acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[cur][n], fa[cur][m], acc[m][n], ca, cb, 0, (int)sb[q][n], 0, (int)sa[q][m]);
-                    else
-                        acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[cur][n], fa[cur][m], acc[m][n], ca, cb, 2, (int)sb[q][n], 2, (int)sa[q][m]);
-                }
+                for (int m = 0; m < MB; ++m)
+#pragma unroll
+                    for (int n = 0; n < NB; ++n) {
+                        if ((ks & 1) == 0)
+                            acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[k][n], fa[k][m], acc[m][n], ca, cb, 0, (int)sb[n], 0, (int)sa[m]);
+                        else
+                            acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[k][n], fa[k][m], acc[m][n], ca, cb, 2, (int)sb[n], 2, (int)sa[m]);
+                    }
+            }
+            __builtin_amdgcn_s_setprio(0);
+        };
+#define SNIP_BAR() do { __builtin_amdgcn_sched_barrier(0); __builtin_amdgcn_s_barrier(); __builtin_amdgcn_sched_barrier(0); } while (0)
+        issue(0, 0);
+        if (wave < NWAVE / 2) {
+            for (int s = 0; s < nstage; ++s) {
+                const int slot = s & 1;
+                SNIP_WAIT_VM(0); SNIP_BAR();                       // b(4s)
+                if (s + 1 < nstage) issue(s + 1, slot ^ 1);
+                R(slot, 0); SNIP_BAR();                            // b(4s+1)
+                M(0);       SNIP_BAR();                            // b(4s+2)
+                R(slot, 1); SNIP_BAR();                            // b(4s+3)
+                M(1);
+            }
+            SNIP_BAR();                                            // b(4S)
+        } else {
+            SNIP_WAIT_VM(0); SNIP_BAR();                           // b(0)
+            for (int s = 0; s < nstage; ++s) {
+                const int slot = s & 1;
+                SNIP_BAR();                                        // b(4s+1)
+                if (s + 1 < nstage) issue(s + 1, slot ^ 1);
+                R(slot, 0); SNIP_BAR();                            // b(4s+2)
+                M(0);       SNIP_BAR();                            // b(4s+3)
+                R(slot, 1); SNIP_WAIT_VM(0); SNIP_BAR();           // b(4s+4)
+                M(1);
+            }
         }
-    };
-
-    // ---- pipeline: iteration s waits for stage s, lets everyone see it, refills the slot freed one
-    //      iteration ago with stage s + NST - 1, and computes.  One basic block per iteration (the slot
-    //      index is a run-time scalar) so that the accumulators never cross a control-flow join. ----
-#pragma unroll
-    for (int st = 0; st < NST - 1; ++st) issue(st, st);
-    int slot = 0;
-    for (int s = 0; s < nstage; ++s) {
-        if (SNIP_EXP != 5) SNIP_WAIT_VM((NST - 2) * C::L);
-        __builtin_amdgcn_s_barrier();
-        const int fill = slot == 0 ? NST - 1 : slot - 1;       // (slot + NST - 1) % NST
-        if (NST > 2 || s + 1 < nstage) issue(s + NST - 1, fill);
-        compute(slot);
-        slot = slot + 1 == NST ? 0 : slot + 1;
+#undef SNIP_BAR
     }
     SNIP_WAIT_VM(0);            // no copy may still be in flight when the LDS is reused below or handed to another workgroup
     __builtin_amdgcn_s_barrier();
-    if (SNIP_EXP == 1 && I > 1) return;
 
     // ---- epilogue: every wave transposes its 128 x 64 block through its own 16 KB of LDS ----
     // In registers, lane (r32, g) of block (m, n) holds C[32m + r32][32n + 8q + 4g + t] in acc[m][n][4q + t].
