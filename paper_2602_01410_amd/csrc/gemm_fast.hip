@@ -10,16 +10,23 @@
 //   The eight waves run a ping-pong schedule: the two waves of a SIMD alternate between reading
 //   their operands of a phase from LDS and issuing that phase's MFMAs, one phase apart, separated by
 //   workgroup barriers, so that the matrix core of every SIMD always has a wave with operands ready.
+//   A wave issues its global -> LDS copies between the MFMAs of one of its MFMA phases, where issue
+//   slots are free (an MFMA occupies the matrix core for 32 or 64 cycles, a copy instruction costs the
+//   wave about 40); issued in front of the LDS reads they made that phase the longest of the four.
 //   LDS rows are unpadded; the 16-byte chunks of a row are XOR-swizzled on the global-address side
 //   of the copy so that the 16 lanes served together by a ds_read_b128 hit 16 different bank groups.
 //   The result tile leaves through LDS as well: each wave transposes its 128 x 64 block so that the
 //   global stores are 16 bytes per lane and 128 contiguous bytes per row.
 //
-// The bound that shapes this kernel is L2 -> LDS bandwidth, not the matrix cores: a 256 x 256 tile
-// needs 64 KB per stage, and the 256 CUs together draw about 20 TB/s from L2 at the FP4 MFMA peak.
+// Measured with shader-clock stamps around every phase (FP4 x FP4, 256 contraction elements per
+// stage): an MFMA phase takes 505 cycles (16 MFMAs x 32), a read phase 390 (one wave issues a
+// ds_read_b128 about every 29 cycles whatever the other waves do), a barrier 40-60.  Under load
+// the clock sits near 1.45 GHz on random codes (1.8 GHz on all-zero codes): the kernel is limited by
+// power, so removing idle cycles gains less than proportionally.
 //
 // See gemm.hip for the register layout of v_mfma_scale_f32_32x32x64_f8f6f4.
 #include "snip_internal.h"
+#include <type_traits>
 
 namespace snip {
 namespace {
@@ -200,6 +207,14 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
         for (int j = 0; j < C::LS; ++j) glds4(sbase[j] + st * sstep[j], os[j], base + C::A_BYTES + C::B_BYTES + (wave * C::LS + j) * 256);
     };
 
+    // copy instruction j (0 .. L-1) of this wave's share of a stage
+    auto issue_one = [&](int j, int stage, int slot) {
+        const unsigned base = lds0 + slot * C::SLOT;
+        if (j < C::LA) glds16(abase + (int64_t)stage * C::SBA, oa[j], base + (wave * C::LA + j) * 1024);
+        else if (j < C::LA + C::LB) { const int k = j - C::LA; glds16(bbase + (int64_t)stage * C::SBB, ob[k], base + C::A_BYTES + (wave * C::LB + k) * 1024); }
+        else { const int k = j - C::LA - C::LB; glds4(sbase[k] + stage * sstep[k], os[k], base + C::A_BYTES + C::B_BYTES + (wave * C::LS + k) * 256); }
+    };
+
     // ---- per-lane LDS read offsets ----
     constexpr int NCA = FA == kFP8 ? 2 * C::KS : C::KS, NCB = FB == kFP8 ? 2 * C::KS : C::KS;
     int offa[NCA], offb[NCB];
@@ -225,7 +240,8 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
     //          group 0        R0(0)   M0(0)   R1(0)   M1(0)   R0(1)   M0(1)
     //          group 1        -       R0(0)   M0(0)   R1(0)   M1(0)   R0(1)
     //      Stage s is complete in LDS before b(4s): every wave waits for its own copies before that barrier.
-    //      The slot of stage s-1 is free after b(4s) (group 1 finished R1(s-1) before it). ----
+    //      The slot of stage s is free after b(4s+4): group 1, the last reader, waits for its R1(s) data
+    //      before that barrier, so no read of the slot is in flight when the first copy into it is issued. ----
     {
         constexpr int KP = C::KS / 2;                      // k-steps per phase
         v8i fa[KP][MB], fb[KP][NB];
@@ -247,9 +263,14 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                 for (int n = 0; n < NB; ++n) fb[k][n] = read_frag<FB>(tb, n * 32 * C::SBB, offb, p * KP + k);
             }
         };
-        auto M = [&](int p) {
+        // The MFMAs of phase p.  With COPY the wave's L copy instructions of stage `nxt` into `nslot` are
+        // spread evenly between the phase's NM MFMAs (the sched_barriers keep them there).
+        constexpr int NM = KP * MB * NB;
+        auto M = [&](auto copy_tag, int p, int nxt, int nslot) {
+            constexpr bool COPY = decltype(copy_tag)::value;
             constexpr int ca = FB == kFP8 ? 0 : 4, cb = FA == kFP8 ? 0 : 4;
             __builtin_amdgcn_s_setprio(1);
+            int idx = 0;
 #pragma unroll
             for (int k = 0; k < KP; ++k) {
                 const int ks = p * KP + k;
@@ -261,34 +282,53 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                             acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[k][n], fa[k][m], acc[m][n], ca, cb, 0, (int)sb[n], 0, (int)sa[m]);
                         else
                             acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[k][n], fa[k][m], acc[m][n], ca, cb, 2, (int)sb[n], 2, (int)sa[m]);
+                        if (COPY) {
+                            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                            for (int j = 0; j < C::L; ++j)
+                                if (j * NM / C::L == idx) issue_one(j, nxt, nslot);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        ++idx;
                     }
             }
             __builtin_amdgcn_s_setprio(0);
         };
+        const std::true_type with_copy{};
+        const std::false_type no_copy{};
 #define SNIP_BAR() do { __builtin_amdgcn_sched_barrier(0); __builtin_amdgcn_s_barrier(); __builtin_amdgcn_sched_barrier(0); } while (0)
         issue(0, 0);
         if (wave < NWAVE / 2) {
-            for (int s = 0; s < nstage; ++s) {
+            // group 0 issues its copies of stage s+1 during M0(s), between b(4s+1) and b(4s+2)
+            auto stage0 = [&](auto copy_tag, int s) {
                 const int slot = s & 1;
                 SNIP_WAIT_VM(0); SNIP_BAR();                       // b(4s)
-                if (s + 1 < nstage) issue(s + 1, slot ^ 1);
                 R(slot, 0); SNIP_BAR();                            // b(4s+1)
-                M(0);       SNIP_BAR();                            // b(4s+2)
+                M(copy_tag, 0, s + 1, slot ^ 1); SNIP_BAR();       // b(4s+2)
                 R(slot, 1); SNIP_BAR();                            // b(4s+3)
-                M(1);
-            }
+                M(no_copy, 1, 0, 0);
+            };
+            for (int s = 0; s < nstage - 1; ++s) stage0(with_copy, s);
+            stage0(no_copy, nstage - 1);
             SNIP_BAR();                                            // b(4S)
         } else {
-            SNIP_WAIT_VM(0); SNIP_BAR();                           // b(0)
-            for (int s = 0; s < nstage; ++s) {
+            // group 1 issues its copies of stage s+2 during M1(s), between b(4s+4) and b(4s+5); those of
+            // stage 1 while it idles through the first phase
+            auto stage1 = [&](auto copy_tag, int s) {
                 const int slot = s & 1;
                 SNIP_BAR();                                        // b(4s+1)
-                if (s + 1 < nstage) issue(s + 1, slot ^ 1);
                 R(slot, 0); SNIP_BAR();                            // b(4s+2)
-                M(0);       SNIP_BAR();                            // b(4s+3)
-                R(slot, 1); SNIP_WAIT_VM(0); SNIP_BAR();           // b(4s+4)
-                M(1);
-            }
+                M(no_copy, 0, 0, 0); SNIP_BAR();                   // b(4s+3)
+                R(slot, 1);
+                __builtin_amdgcn_s_waitcnt(0x0070);                // vmcnt(0) and lgkmcnt(0)
+                SNIP_BAR();                                        // b(4s+4)
+                M(copy_tag, 1, s + 2, slot);
+            };
+            SNIP_WAIT_VM(0); SNIP_BAR();                           // b(0)
+            if (nstage > 1) issue(1, 1);
+            for (int s = 0; s < nstage - 2; ++s) stage1(with_copy, s);
+            if (nstage > 1) stage1(no_copy, nstage - 2);
+            stage1(no_copy, nstage - 1);
         }
 #undef SNIP_BAR
     }
