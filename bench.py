@@ -95,23 +95,26 @@ class Layer:
         snip = self.snip
         fn = {"fwd": snip.snip_gemm_fwd, "dgrad": snip.snip_gemm_dgrad, "wgrad": snip.snip_gemm_wgrad}
 
+        # One HIP event in front of every call and one behind the last: a call's duration is the distance
+        # to the next event, on the stream the kernels are launched on.
         def timed(tag, f):
-            if ev is None:
-                f()
-                return
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
+            if ev is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                ev.append((tag, e))
             f()
-            b.record()
-            ev.append((tag, a, b))
 
         for (key, fmt, axis), st in self.qjobs:
-            timed(("q", fmt, axis), lambda: snip.snip_quantize(self.src[key], fmt, axis, out=self.q[(key, fmt, axis)],
-                                                             stats=st, workspace=self.ws))
+            timed(("q", key[0] == "W"), lambda: snip.snip_quantize(self.src[key], fmt, axis, out=self.q[(key, fmt, axis)],
+                                                                  stats=st, workspace=self.ws))
         for name, pc, a, b, out, fl, fmts in self.gjobs:
             timed(("g", fmts, fl), lambda: fn[name](pc, a, b, out=out))
         for key, axis, st in self.sjobs:
             timed(("s", axis), lambda: snip.snip_quant_error_stats(self.src[key], axis, out=st, workspace=self.ws))
+        if ev is not None:
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            ev.append((("end",), e))
 
 
 def cpu_baseline(cfg, wl):
@@ -165,13 +168,18 @@ def main():
     ms_per_step = wall / args.steps * 1e3
 
     # per-kernel figures from the HIP events recorded on the launch stream inside the timed region
-    agg = {}
-    for tag, a, b in events:
+    agg = {"qw": [0.0, 0, 0.0]}
+    for (tag, a), (_, b) in zip(events[:-1], events[1:]):
+        if tag[0] == "end":
+            continue
+        sec = a.elapsed_time(b) * 1e-3
         d = agg.setdefault(tag[0] if tag[0] != "g" else ("g", tag[1]), [0.0, 0, 0.0])
-        d[0] += a.elapsed_time(b) * 1e-3
+        d[0] += sec
         d[1] += 1
         if tag[0] == "g":
             d[2] += tag[2]
+        if tag[0] == "q" and tag[1]:
+            agg["qw"][0] += sec
     gem = {k[1]: v for k, v in agg.items() if isinstance(k, tuple)}
     dom = max(gem, key=lambda k: gem[k][0])
     dsec, dn, dfl = gem[dom]
@@ -180,6 +188,7 @@ def main():
     gemm_sec = sum(v[0] for v in gem.values()) / args.steps
     q_sec = agg["q"][0] / args.steps
     s_sec = agg["s"][0] / args.steps
+    qw_sec = agg["qw"][0] / args.steps          # quantizations of weights (change once per optimizer step)
     plan_peak = wl.plan_peak_flops(cfg, plan, PEAK["fp4"], PEAK["fp8"])
     value = layer.flops / (ms_per_step * 1e-3) / 1e12
 
@@ -197,6 +206,9 @@ def main():
         "quantize_gbps": layer.q_bytes / q_sec / 1e9, "quantize_pct_hbm": 100.0 * layer.q_bytes / q_sec / PEAK["hbm"],
         "stats_gbps": layer.s_bytes / s_sec / 1e9, "stats_pct_hbm": 100.0 * layer.s_bytes / s_sec / PEAK["hbm"],
         "ms_gemm": gemm_sec * 1e3, "ms_quantize": q_sec * 1e3, "ms_stats": s_sec * 1e3,
+        # the two accountings of "incl. quantize" without the stand-alone statistics pass
+        "gemm_plus_quantize_tflops": layer.flops / (gemm_sec + q_sec) / 1e12,
+        "gemm_plus_quantize_w_amortised_tflops": layer.flops / (gemm_sec + q_sec - qw_sec) / 1e12,
         "input_generation_s": layer.gen_seconds,
         "roofline": {"bound": "mfma", "kernel": KERNEL_NAME[dom], "achieved": achieved / 1e12, "peak": peak / 1e12,
                      "unit": "TFLOP/s", "frac": achieved / peak,

@@ -74,3 +74,31 @@ def test_stats_deterministic_and_empty():
     out = snip.snip_quant_error_stats(x, snip.ROW)
     torch.cuda.synchronize()
     assert host(out).tolist() == [0.0, 0.0, 0.0]
+
+
+@pytest.mark.parametrize("fill", [0x00, 0xFF, "random"])
+def test_stats_workspace_needs_no_initialisation_and_is_reusable(fill):
+    """Whatever bytes the workspace holds before the first call, and across calls of different kernels
+    and grid shapes that share it, the results stay right."""
+    snip = require_gpu()
+    rng = np.random.default_rng(33)
+    shapes = [(512, 1024), (96, 4096), (2048, 256)]
+    tensors = [wl.f32_to_bf16_bits(rng.standard_normal(s).astype(np.float32)) for s in shapes]
+    ws = snip.alloc_workspace(2048, 4096)
+    if fill == "random":
+        ws.copy_(torch.from_numpy(rng.integers(0, 256, size=ws.numel(), dtype=np.uint8)).cuda())
+    else:
+        ws.fill_(fill)
+    for rep in range(2):
+        for bits in tensors:
+            x = to_dev(bits)
+            for axis in (oracle.ROW, oracle.COL):
+                want = oracle.stats(bits, axis)
+                out = snip.snip_quant_error_stats(x, axis, workspace=ws)
+                st = snip.alloc_stats()
+                snip.snip_quantize(x, snip.FP4, axis, stats=st, workspace=ws)
+                torch.cuda.synchronize()
+                np.testing.assert_allclose(host(out), want, rtol=TOL)
+                f = host(st)
+                np.testing.assert_allclose(f[:2], want[:2], rtol=TOL)
+                assert np.isnan(f[2])
