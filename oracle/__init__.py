@@ -68,6 +68,12 @@ def _load():
             fn.argtypes = [vp, vp, i64, i64, i64, vp]
         lib.oracle_stats.restype = ci
         lib.oracle_stats.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp]
+        lib.oracle_round_output.restype = dbl
+        lib.oracle_round_output.argtypes = [dbl, ci]
+        lib.oracle_output_sum_sq.restype = dbl
+        lib.oracle_output_sum_sq.argtypes = [vp, i64, ci]
+        lib.oracle_loss_divergence.restype = dbl
+        lib.oracle_loss_divergence.argtypes = [dbl, dbl, i64, dbl, dbl, i64, i64]
         _lib = lib
     return _lib
 
@@ -208,3 +214,24 @@ def stats(x_bf16_bits, axis: int = ROW, rule: int = NO_OVERFLOW, per_line: bool 
     _check(_load().oracle_stats(_ptr(x), rows, cols, cols, axis, rule, _ptr(out),
                                 _ptr(lines) if per_line else None), "stats")
     return (out, lines) if per_line else out
+
+
+OUT_BF16, OUT_FP32 = 0, 1
+
+
+def round_output(v: float, out_dtype: int = OUT_BF16) -> float:
+    """Nearest bf16 (or fp32) value, ties to even."""
+    return float(_load().oracle_round_output(float(v), out_dtype))
+
+
+def output_sum_sq(c, out_dtype: int = OUT_BF16) -> float:
+    """Squared Frobenius norm of a GEMM output after rounding every element to the output type."""
+    a = np.ascontiguousarray(np.asarray(c, dtype=np.float64))
+    return float(_load().oracle_output_sum_sq(_ptr(a), a.size, out_dtype))
+
+
+def loss_divergence(grad_x_sq: float, err_x_sq: float, M: int, grad_w_sq: float, err_w_sq: float,
+                    N: int, K: int) -> float:
+    """Loss-divergence estimate of one linear layer from squared Frobenius norms."""
+    return float(_load().oracle_loss_divergence(float(grad_x_sq), float(err_x_sq), M,
+                                                float(grad_w_sq), float(err_w_sq), N, K))

@@ -17,6 +17,8 @@
  *   - Sec. 4.1 / 4.3.1 notation: X in R^{M x K}, W in R^{N x K}, dY in R^{M x N}.
  *   - Sec. 3.1 Step 1: Frobenius norms of the tensors and of their quantization error.
  *   - Sec. 5.3 "Memory Overhead": the row-wise form of those norms.
+ *   - Sec. 4.2 "Loss Divergence in Forward Pass": the per-layer estimate built from the
+ *     norms of dX, dW and of the quantization errors of X and W.
  *
  * All arithmetic is IEEE double or integer.  Everything a bf16 tensor can hold, and every
  * FP8/FP4 grid value times a power of two, is exact in double, so quantization here has
@@ -333,4 +335,49 @@ int oracle_stats(const uint16_t* src, int64_t rows, int64_t cols, int64_t ld,
     }
     free(q4); free(q8); free(line);
     return rc;
+}
+
+/* ---- norms of the GEMM outputs and the loss-divergence estimate ---------------------- */
+
+/* Nearest value representable in the GEMM's output type, ties to even: out_dtype 0 = bf16
+ * (8 significant bits, the exponent range of an IEEE single), 1 = IEEE single.  The bf16
+ * rounding is done on the double directly (scale so that one unit in the last place is 1,
+ * round to the nearest integer with ties to even, scale back).  Magnitudes beyond the
+ * type's largest finite value are outside what the path produces and are not handled. */
+double oracle_round_output(double v, int out_dtype)
+{
+    if (out_dtype == 1) return (double)(float)v;
+    if (v == 0.0 || isnan(v) || isinf(v)) return v;
+    int e;
+    (void)frexp(fabs(v), &e);                /* |v| = f * 2^e, 0.5 <= f < 1  =>  exponent of v is e-1 */
+    int ex = e - 1;
+    if (ex < -126) ex = -126;                /* subnormal range: fixed quantum 2^-133 */
+    double quantum = ldexp(1.0, ex - 7);     /* 8 significant bits */
+    return nearbyint(v / quantum) * quantum; /* default rounding mode: to nearest, ties to even */
+}
+
+/* Squared Frobenius norm of a GEMM output as the path stores it (Sec. 3.1 Step 1 lists the
+ * norms of Y, dX and dW among the collected statistics): every element of the exact product
+ * c[0..n) is rounded to the output type, squared and summed in index order in double. */
+double oracle_output_sum_sq(const double* c, int64_t n, int out_dtype)
+{
+    double s = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double r = oracle_round_output(c[i], out_dtype);
+        s += r * r;
+    }
+    return s;
+}
+
+/* Estimated change of the loss when the inputs X [M,K] and weights W [N,K] of one linear
+ * layer are quantized (Sec. 4.2 "Loss Divergence in Forward Pass"):
+ *     sqrt( (|grad_X L| |delta_X| / sqrt(M K))^2 + (|grad_W L| |delta_W| / sqrt(N K))^2 )
+ * with Frobenius norms; the arguments are SQUARED norms, as the statistics deliver them
+ * (grad_X L is the dgrad output, grad_W L the wgrad output, delta = q(.) - .). */
+double oracle_loss_divergence(double grad_x_sq, double err_x_sq, int64_t M,
+                              double grad_w_sq, double err_w_sq, int64_t N, int64_t K)
+{
+    double tx = sqrt(grad_x_sq) * sqrt(err_x_sq) / sqrt((double)M * (double)K);
+    double tw = sqrt(grad_w_sq) * sqrt(err_w_sq) / sqrt((double)N * (double)K);
+    return sqrt(tx * tx + tw * tw);
 }
