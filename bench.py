@@ -37,6 +37,8 @@ def parse():
     p.add_argument("--config", type=int, default=4, help="workload configuration 1..5 (default: Llama-7B-shaped layer)")
     p.add_argument("--plan", type=str, default=None, help="fp4 | fp8 | mixNN | tensor (default: the config's mixed plan)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--output-norms", action="store_true",
+                   help="use the GEMM variants that also return the squared Frobenius norm of Y, dX, dW")
     p.add_argument("--microbench", action="store_true",
                    help="run the device microbenchmarks (measured MFMA / HBM / L2 rates) and exit")
     return p.parse_args()
@@ -45,8 +47,9 @@ def parse():
 class Layer:
     """Device tensors, pre-allocated outputs and the launch list of one step."""
 
-    def __init__(self, cfg, plan, snip, wl):
+    def __init__(self, cfg, plan, snip, wl, output_norms=False):
         self.cfg, self.plan, self.snip = cfg, plan, snip
+        self.output_norms = output_norms
         dev = "cuda"
 
         def up(bits):
@@ -87,6 +90,10 @@ class Layer:
             self.gjobs.append(("wgrad", pc, need(kdy, e[4], snip.COL), need(kx, e[5], snip.COL),
                                torch.empty((l.N, l.K), dtype=torch.bfloat16, device=dev), 2 * M * l.N * l.K, (e[4], e[5])))
         self.sjobs = [(key, axis, snip.alloc_stats()) for key in self.src for axis in (snip.ROW, snip.COL)]
+        if output_norms:
+            self.gws = torch.empty(max(snip.gemm_workspace_bytes(j[4].shape[0], j[4].shape[1]) for j in self.gjobs),
+                                   dtype=torch.uint8, device=dev)
+            self.gnorm = [torch.empty(1, dtype=torch.float64, device=dev) for _ in self.gjobs]
         self.flops = sum(j[5] for j in self.gjobs)
         self.q_bytes = sum(self.src[k[0]].numel() * (2 + (1.0 if k[1] == snip.FP8 else 0.5) + 1 / 32) for k, _ in self.qjobs)
         self.s_bytes = sum(self.src[key].numel() * 2 for key, _, _ in self.sjobs)
@@ -107,8 +114,12 @@ class Layer:
         for (key, fmt, axis), st in self.qjobs:
             timed(("q", key[0] == "W"), lambda: snip.snip_quantize(self.src[key], fmt, axis, out=self.q[(key, fmt, axis)],
                                                                   stats=st, workspace=self.ws))
-        for name, pc, a, b, out, fl, fmts in self.gjobs:
-            timed(("g", fmts, fl), lambda: fn[name](pc, a, b, out=out))
+        fn_norm = {"fwd": snip.snip_gemm_fwd_norm, "dgrad": snip.snip_gemm_dgrad_norm, "wgrad": snip.snip_gemm_wgrad_norm}
+        for gi, (name, pc, a, b, out, fl, fmts) in enumerate(self.gjobs):
+            if self.output_norms:
+                timed(("g", fmts, fl), lambda: fn_norm[name](pc, a, b, out=out, sum_sq=self.gnorm[gi], workspace=self.gws))
+            else:
+                timed(("g", fmts, fl), lambda: fn[name](pc, a, b, out=out))
         for key, axis, st in self.sjobs:
             timed(("s", axis), lambda: snip.snip_quant_error_stats(self.src[key], axis, out=st, workspace=self.ws))
         if ev is not None:
@@ -154,7 +165,7 @@ def main():
     plan_name = args.plan or next((p for p in cfg.plans if p.startswith("mix")), cfg.plans[0])
     plan = wl.make_plan(cfg, plan_name)
     torch.cuda.set_device(0)
-    layer = Layer(cfg, plan, snip, wl)
+    layer = Layer(cfg, plan, snip, wl, args.output_norms)
 
     for _ in range(args.warmup):
         layer.step()
@@ -199,7 +210,8 @@ def main():
         "dtype": "fp4_e2m1+fp8_e4m3 (fp32 accumulate, bf16 out)", "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}, {cfg.M} tokens, 7 linears x (fwd, dgrad, wgrad) "
                                f"+ all quantizations + statistics pass", "plan": plan_name,
-                   "fp4_flop_fraction": wl.plan_fp4_fraction(cfg, plan), "layer_flop": layer.flops},
+                   "fp4_flop_fraction": wl.plan_fp4_fraction(cfg, plan), "layer_flop": layer.flops,
+                   "output_norms": bool(args.output_norms)},
         "pct_of_plan_peak": 100.0 * value * 1e12 / plan_peak,
         "gemm_only_tflops": layer.flops / gemm_sec / 1e12,
         "gemm_only_pct_of_plan_peak": 100.0 * layer.flops / gemm_sec / plan_peak,

@@ -155,6 +155,40 @@ snip_status snip_gemm_wgrad(const snip_layer_plan* plan, const snip_qtensor* dyq
                             snip_out_dtype out_dtype, void* workspace, size_t workspace_bytes,
                             void* stream);
 
+/* ---- GEMMs that also deliver the norm of their output (Sec. 3.1 Step 1) --------------- */
+/* Step 1 of the paper collects the Frobenius norms of Y, dX and dW next to those of the GEMM
+ * inputs; ||dX|| and ||dW|| are the gradient factors of the loss-divergence estimate (Sec. 4.2
+ * "Loss Divergence in Forward Pass").  These variants compute exactly what the plain calls do and,
+ * from the same accumulators, the squared Frobenius norm of the output AS STORED (every element
+ * rounded to the output type first; elements outside the matrix do not count).
+ *   sum_sq   : device, one double.
+ *   workspace: device, required, >= snip_gemm_workspace_bytes(out rows, out cols) bytes, 16-byte
+ *              aligned, no initialisation needed; calls that overlap in time must not share it.
+ * The sum is formed per lane (128 or 64 squares), per wave and per workgroup in fp32 and across
+ * workgroups in double, all in a fixed order: results are identical from run to run. */
+size_t snip_gemm_workspace_bytes(int64_t out_rows, int64_t out_cols);
+snip_status snip_gemm_fwd_norm(const snip_layer_plan* plan, const snip_qtensor* xq_row,
+                               const snip_qtensor* wq_row, void* y, int64_t ld_out,
+                               snip_out_dtype out_dtype, double* sum_sq, void* workspace,
+                               size_t workspace_bytes, void* stream);
+snip_status snip_gemm_dgrad_norm(const snip_layer_plan* plan, const snip_qtensor* dyq_row,
+                                 const snip_qtensor* wq_col, void* dx, int64_t ld_out,
+                                 snip_out_dtype out_dtype, double* sum_sq, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+snip_status snip_gemm_wgrad_norm(const snip_layer_plan* plan, const snip_qtensor* dyq_col,
+                                 const snip_qtensor* xq_col, void* dw, int64_t ld_out,
+                                 snip_out_dtype out_dtype, double* sum_sq, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/* Host, pure.  The paper's estimate of the loss change caused by quantizing the inputs X [m,k]
+ * and weights W [n,k] of one linear layer (Sec. 4.2 "Loss Divergence in Forward Pass"):
+ *     sqrt( (||dX|| ||q(X)-X|| / sqrt(m k))^2 + (||dW|| ||q(W)-W|| / sqrt(n k))^2 )
+ * from SQUARED Frobenius norms: grad_x_sq / grad_w_sq are the sum_sq of the dgrad / wgrad calls
+ * above, err_x_sq / err_w_sq the err_sq_* fields of snip_stats for the format in question.
+ * Returns NaN for a non-positive extent or a negative or NaN argument. */
+double snip_loss_divergence(double grad_x_sq, double err_x_sq, int64_t m,
+                            double grad_w_sq, double err_w_sq, int64_t n, int64_t k);
+
 /* ---- quantization-error statistics (Sec. 3.1 Step 1; row-wise form: Sec. 5.3) -------- */
 
 /* One read of a bf16 matrix; for blocks along `axis` produces the squared Frobenius norm of x

@@ -1,6 +1,7 @@
 // C-ABI layer: argument validation and dispatch.  No kernel code here.
 #include "../../include/snip.h"
 #include "snip_internal.h"
+#include <cmath>
 
 using namespace snip;
 
@@ -27,7 +28,8 @@ snip_status check_source(const void* x, int64_t rows, int64_t cols, int64_t ld, 
 
 snip_status check_qtensor(const snip_qtensor* q)
 {
-    if (!q || !q->codes || !q->scales) return SNIP_ERR_NULL;
+    if (!q) return SNIP_ERR_NULL;
+    if ((!q->codes || !q->scales) && q->rows > 0) return SNIP_ERR_NULL;      // an empty matrix may have no storage
     if (!valid_fmt(q->fmt)) return SNIP_ERR_FORMAT;
     if (q->rows < 0 || q->cols <= 0 || q->cols % 32 != 0) return SNIP_ERR_SHAPE;
     if (q->rows >= (int64_t)1 << 31 || q->cols >= (int64_t)1 << 31) return SNIP_ERR_SHAPE;
@@ -37,14 +39,17 @@ snip_status check_qtensor(const snip_qtensor* q)
     return SNIP_OK;
 }
 
+size_t gemm_ws_bytes(int64_t I, int64_t J) { return (size_t)gemm_norm_partials(I, J) * sizeof(float) + 16; }
+
 snip_status gemm(const snip_qtensor* a, int fmt_a, const snip_qtensor* b, int fmt_b, void* c, int64_t ldc,
-                 int out_dtype, void* stream)
+                 int out_dtype, void* stream, bool want_norm = false, double* sum_sq = nullptr,
+                 void* workspace = nullptr, size_t workspace_bytes_ = 0)
 {
     snip_status st = check_qtensor(a);
     if (st != SNIP_OK) return st;
     st = check_qtensor(b);
     if (st != SNIP_OK) return st;
-    if (!c) return SNIP_ERR_NULL;
+    if (!c && a->rows > 0 && b->rows > 0) return SNIP_ERR_NULL;
     if (!valid_fmt(fmt_a) || !valid_fmt(fmt_b)) return SNIP_ERR_FORMAT;
     if (out_dtype != SNIP_OUT_BF16 && out_dtype != SNIP_OUT_FP32) return SNIP_ERR_FORMAT;
     if (a->fmt != fmt_a || b->fmt != fmt_b) return SNIP_ERR_FORMAT;
@@ -58,6 +63,13 @@ snip_status gemm(const snip_qtensor* a, int fmt_a, const snip_qtensor* b, int fm
     g.b_codes = (const uint8_t*)b->codes; g.b_scales = b->scales; g.b_scales_g4 = b->scales_g4; g.fmt_b = fmt_b;
     g.I = a->rows; g.J = b->rows; g.R = a->cols;
     g.c = c; g.ldc = ldc; g.out_fp32 = out_dtype == SNIP_OUT_FP32;
+    if (want_norm) {
+        if (!sum_sq) return SNIP_ERR_NULL;
+        if (!workspace || workspace_bytes_ < gemm_ws_bytes(g.I, g.J)) return SNIP_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return SNIP_ERR_LAYOUT;
+        g.norm_partials = (float*)workspace;
+        g.norm_out = sum_sq;
+    }
     return launch_gemm(g, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
 }
 
@@ -136,6 +148,47 @@ snip_status snip_gemm_wgrad(const snip_layer_plan* plan, const snip_qtensor* dyq
 {
     if (!plan) return SNIP_ERR_NULL;
     return gemm(dyq_col, plan->wgrad_dy, xq_col, plan->wgrad_x, dw, ld_out, out_dtype, stream);
+}
+
+size_t snip_gemm_workspace_bytes(int64_t out_rows, int64_t out_cols)
+{
+    if (out_rows < 0 || out_cols < 0) return 0;
+    return gemm_ws_bytes(out_rows, out_cols);
+}
+
+snip_status snip_gemm_fwd_norm(const snip_layer_plan* plan, const snip_qtensor* xq_row, const snip_qtensor* wq_row,
+                               void* y, int64_t ld_out, snip_out_dtype out_dtype, double* sum_sq, void* workspace,
+                               size_t workspace_bytes_, void* stream)
+{
+    if (!plan) return SNIP_ERR_NULL;
+    return gemm(xq_row, plan->fwd_x, wq_row, plan->fwd_w, y, ld_out, out_dtype, stream, true, sum_sq, workspace, workspace_bytes_);
+}
+
+snip_status snip_gemm_dgrad_norm(const snip_layer_plan* plan, const snip_qtensor* dyq_row, const snip_qtensor* wq_col,
+                                 void* dx, int64_t ld_out, snip_out_dtype out_dtype, double* sum_sq, void* workspace,
+                                 size_t workspace_bytes_, void* stream)
+{
+    if (!plan) return SNIP_ERR_NULL;
+    return gemm(dyq_row, plan->dgrad_dy, wq_col, plan->dgrad_w, dx, ld_out, out_dtype, stream, true, sum_sq, workspace, workspace_bytes_);
+}
+
+snip_status snip_gemm_wgrad_norm(const snip_layer_plan* plan, const snip_qtensor* dyq_col, const snip_qtensor* xq_col,
+                                 void* dw, int64_t ld_out, snip_out_dtype out_dtype, double* sum_sq, void* workspace,
+                                 size_t workspace_bytes_, void* stream)
+{
+    if (!plan) return SNIP_ERR_NULL;
+    return gemm(dyq_col, plan->wgrad_dy, xq_col, plan->wgrad_x, dw, ld_out, out_dtype, stream, true, sum_sq, workspace, workspace_bytes_);
+}
+
+double snip_loss_divergence(double grad_x_sq, double err_x_sq, int64_t m, double grad_w_sq, double err_w_sq,
+                            int64_t n, int64_t k)
+{
+    if (m <= 0 || n <= 0 || k <= 0 || !(grad_x_sq >= 0.0) || !(err_x_sq >= 0.0) || !(grad_w_sq >= 0.0) || !(err_w_sq >= 0.0))
+        return std::nan("");
+    // each term is a product of two Frobenius norms over the square root of the element count
+    const double tx = std::sqrt(grad_x_sq * err_x_sq / ((double)m * (double)k));
+    const double tw = std::sqrt(grad_w_sq * err_w_sq / ((double)n * (double)k));
+    return std::hypot(tx, tw);
 }
 
 snip_status snip_quant_error_stats(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_axis axis,

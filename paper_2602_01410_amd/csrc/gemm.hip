@@ -109,7 +109,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(const uint8_t* __restric
                                                         const uint8_t* __restrict__ b_codes,
                                                         const uint8_t* __restrict__ b_scales,
                                                         int I, int J, int R, void* __restrict__ c_out, int64_t ldc,
-                                                        int tiles_i, int tiles_j)
+                                                        int tiles_i, int tiles_j, float* __restrict__ norm_partials)
 {
     using C = Cfg<FA, FB>;
     __shared__ __attribute__((aligned(16))) uint8_t lds_a[BM * C::PA];
@@ -210,6 +210,34 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(const uint8_t* __restric
         }
     }
 
+    // Optional: sum of squares of the tile as it will be stored (rounded to the output type), elements
+    // outside the matrix excluded; one partial per workgroup, combined by reduce_norm_kernel.
+    if (norm_partials) {
+        float ss = 0.f;
+#pragma unroll
+        for (int ib = 0; ib < 2; ++ib) {
+            const bool row_ok = i0 + wm * WM + ib * 32 + r32 < I;
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const int col = j0 + wn * WN + jb * 32 + 8 * (k >> 2) + 4 * g + (k & 3);
+                    float v = acc[ib][jb][k];
+                    if (!OUT_F32) v = (float)(__bf16)v;
+                    ss = (row_ok && col < J) ? fmaf(v, v, ss) : ss;
+                }
+        }
+        for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+        __shared__ float wave_ss[NTHREADS / 64];
+        if (lane == 0) wave_ss[wave] = ss;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float t = 0.f;
+            for (int w = 0; w < NTHREADS / 64; ++w) t += wave_ss[w];
+            norm_partials[blockIdx.x] = t;
+        }
+    }
+
     // Epilogue: lane owns row i, register quad q owns columns 8q + 4g .. +3 of each 32-wide block.
 #pragma unroll
     for (int ib = 0; ib < 2; ++ib) {
@@ -249,23 +277,58 @@ hipError_t launch_t(const GemmArgs& a, hipStream_t s)
     const dim3 grid((unsigned)(ti * tj)), block(NTHREADS);
     if (a.out_fp32)
         hipLaunchKernelGGL((gemm_kernel<FA, FB, true>), grid, block, 0, s, a.a_codes, a.a_scales, a.b_codes, a.b_scales,
-                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj);
+                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj, a.norm_partials);
     else
         hipLaunchKernelGGL((gemm_kernel<FA, FB, false>), grid, block, 0, s, a.a_codes, a.a_scales, a.b_codes, a.b_scales,
-                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj);
+                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj, a.norm_partials);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
+// Sum of n workgroup partials in index order, in double: one workgroup, thread t adds t, t + 1024, ...,
+// then a shared-memory tree.
+constexpr int kNormThreads = 1024;
+__global__ __launch_bounds__(kNormThreads) void reduce_norm_kernel(const float* __restrict__ partials, int64_t n,
+                                                                   double* __restrict__ out)
 {
-    if (a.I == 0 || a.J == 0) return hipSuccess;
+    __shared__ double sh[kNormThreads];
+    double a = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += kNormThreads) a += (double)partials[i];
+    sh[threadIdx.x] = a;
+    __syncthreads();
+    for (int st = kNormThreads / 2; st > 0; st >>= 1) {
+        if ((int)threadIdx.x < st) sh[threadIdx.x] += sh[threadIdx.x + st];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = sh[0];
+}
+
+static hipError_t launch_gemm_kernel(const GemmArgs& a, hipStream_t s)
+{
     if (gemm_fast_eligible(a)) return launch_gemm_fast(a, s);
     if (a.fmt_a == kFP8 && a.fmt_b == kFP8) return launch_t<kFP8, kFP8>(a, s);
     if (a.fmt_a == kFP8 && a.fmt_b == kFP4) return launch_t<kFP8, kFP4>(a, s);
     if (a.fmt_a == kFP4 && a.fmt_b == kFP8) return launch_t<kFP4, kFP8>(a, s);
     return launch_t<kFP4, kFP4>(a, s);
+}
+
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
+{
+    const bool empty = a.I == 0 || a.J == 0;
+    if (!empty) {
+        const hipError_t e = launch_gemm_kernel(a, s);
+        if (e != hipSuccess) return e;
+    }
+    if (a.norm_out) {
+        int64_t n = 0;
+        if (!empty)
+            n = gemm_fast_eligible(a) ? gemm_fast_partials(a)
+                                      : ((a.I + BM - 1) / BM) * ((a.J + BN - 1) / BN);
+        hipLaunchKernelGGL(reduce_norm_kernel, dim3(1), dim3(kNormThreads), 0, s, (const float*)a.norm_partials, n, a.norm_out);
+        return hipGetLastError();
+    }
+    return hipSuccess;
 }
 
 }  // namespace snip

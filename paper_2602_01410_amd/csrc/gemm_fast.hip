@@ -130,7 +130,7 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                                                        const uint8_t* __restrict__ b_codes,
                                                        const uint8_t* __restrict__ b_g4,
                                                        int I, int J, int R, void* __restrict__ c_out, int64_t ldc,
-                                                       int tiles_i, int tiles_j)
+                                                       int tiles_i, int tiles_j, float* __restrict__ norm_partials)
 {
     using C = FCfg<FA, FB>;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[C::LDS_BYTES];
@@ -335,6 +335,54 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
     SNIP_WAIT_VM(0);            // no copy may still be in flight when the LDS is reused below or handed to another workgroup
     __builtin_amdgcn_s_barrier();
 
+    // ---- optional: sum of squares of the tile as it will be stored (rounded to the output type), elements
+    //      outside the matrix excluded; one partial per workgroup, combined by a second kernel.  Interior
+    //      tiles take the short path: bf16 pairs are squared and added by v_dot2c_f32_bf16. ----
+    if (norm_partials) {
+        __shared__ float wave_ss[NWAVE];
+        float ss = 0.f;
+        if (i0 + TM <= I && j0 + TN <= J) {
+#pragma unroll
+            for (int m = 0; m < MB; ++m)
+#pragma unroll
+                for (int n = 0; n < NB; ++n)
+#pragma unroll
+                    for (int k = 0; k < 16; k += 2) {
+                        if (OUT_F32) {
+                            ss = fmaf(acc[m][n][k], acc[m][n][k], ss);
+                            ss = fmaf(acc[m][n][k + 1], acc[m][n][k + 1], ss);
+                        } else {
+                            const float2_t pr = {acc[m][n][k], acc[m][n][k + 1]};
+                            const bf16x2 r = __builtin_convertvector(pr, bf16x2);
+                            const unsigned rb = __builtin_bit_cast(unsigned, r);
+                            asm("v_dot2c_f32_bf16 %0, %1, %1" : "+v"(ss) : "v"(rb));       // ss += r.x * r.x + r.y * r.y
+                        }
+                    }
+        } else {
+#pragma unroll
+            for (int m = 0; m < MB; ++m) {
+                const bool row_ok = i0 + wm * WTM + m * 32 + r32 < I;
+#pragma unroll
+                for (int n = 0; n < NB; ++n)
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const int col = j0 + wn * WTN + n * 32 + 8 * (k >> 2) + 4 * g + (k & 3);
+                        float v = acc[m][n][k];
+                        if (!OUT_F32) v = (float)(__bf16)v;
+                        ss = (row_ok && col < J) ? fmaf(v, v, ss) : ss;
+                    }
+            }
+        }
+        for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+        if (lane == 0) wave_ss[wave] = ss;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float t = 0.f;
+            for (int w = 0; w < NWAVE; ++w) t += wave_ss[w];
+            norm_partials[blockIdx.x] = t;
+        }
+    }
+
     // ---- epilogue: every wave transposes its 128 x 64 block through its own 16 KB of LDS ----
     // In registers, lane (r32, g) of block (m, n) holds C[32m + r32][32n + 8q + 4g + t] in acc[m][n][4q + t].
     // In LDS a row is ROWB bytes of 16-byte chunks, chunk c of row r stored at position c ^ f(r).
@@ -407,10 +455,10 @@ hipError_t launch_fast_t(const GemmArgs& a, hipStream_t s)
     const dim3 grid((unsigned)(ti * tj)), block(NT);
     if (a.out_fp32)
         hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, true>), grid, block, 0, s, a.a_codes, a.a_scales_g4, a.b_codes, a.b_scales_g4,
-                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj);
+                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj, a.norm_partials);
     else
         hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, false>), grid, block, 0, s, a.a_codes, a.a_scales_g4, a.b_codes, a.b_scales_g4,
-                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj);
+                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj, a.norm_partials);
     return hipGetLastError();
 }
 
@@ -422,6 +470,8 @@ bool gemm_fast_eligible(const GemmArgs& a)
     if (a.R > (1 << 22)) return false;      // per-lane source offsets are 32-bit: 256 rows x row bytes must fit
     return a.a_scales_g4 && a.b_scales_g4 && a.R % ke == 0 && a.R >= ke && a.I > 128 && a.J > 128;
 }
+
+int64_t gemm_fast_partials(const GemmArgs& a) { return ((a.I + TM - 1) / TM) * ((a.J + TN - 1) / TN); }
 
 hipError_t launch_gemm_fast(const GemmArgs& a, hipStream_t s)
 {

@@ -46,7 +46,13 @@ struct GemmArgs {
     const uint8_t* b_codes; const uint8_t* b_scales; const uint8_t* b_scales_g4; int fmt_b;
     int64_t I, J, R;      // C[I][J] = sum_r A[I][r] B[J][r]
     void* c; int64_t ldc; int out_fp32;
+    // optional: squared Frobenius norm of the stored output.  norm_partials has room for
+    // gemm_norm_partials(I, J) floats (one per workgroup of the launch); norm_out is one double.
+    float* norm_partials = nullptr;
+    double* norm_out = nullptr;
 };
+// Upper bound of the number of partials either GEMM kernel writes for an I x J output (128 x 128 tiles).
+inline int64_t gemm_norm_partials(int64_t I, int64_t J) { return ((I + 127) / 128) * ((J + 127) / 128); }
 
 size_t workspace_bytes(int64_t rows, int64_t cols);
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t s);
@@ -54,5 +60,6 @@ hipError_t launch_stats(const StatsArgs& a, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 bool gemm_fast_eligible(const GemmArgs& a);          // 256x256-tile kernel (gemm_fast.hip)
 hipError_t launch_gemm_fast(const GemmArgs& a, hipStream_t s);
+int64_t gemm_fast_partials(const GemmArgs& a);         // partials launch_gemm_fast writes
 
 }  // namespace snip

@@ -24,7 +24,9 @@ OUT_BF16, OUT_FP32 = 0, 1
 EXPORTS = ("snip_qtensor_code_bytes", "snip_qtensor_scale_bytes", "snip_qtensor_scale_g4_bytes",
            "snip_workspace_bytes",
            "snip_quantize", "snip_gemm_fwd", "snip_gemm_dgrad", "snip_gemm_wgrad",
-           "snip_quant_error_stats", "snip_status_string")
+           "snip_quant_error_stats", "snip_status_string",
+           "snip_gemm_workspace_bytes", "snip_gemm_fwd_norm", "snip_gemm_dgrad_norm", "snip_gemm_wgrad_norm",
+           "snip_loss_divergence")
 
 
 class SnipError(RuntimeError):
@@ -71,6 +73,15 @@ def _lib():
             fn.restype = ci
             fn.argtypes = [ctypes.POINTER(_PlanC), ctypes.POINTER(_QTensorC), ctypes.POINTER(_QTensorC),
                            vp, i64, ci, vp, sz, vp]
+        lib.snip_gemm_workspace_bytes.restype = sz
+        lib.snip_gemm_workspace_bytes.argtypes = [i64, i64]
+        for name in ("snip_gemm_fwd_norm", "snip_gemm_dgrad_norm", "snip_gemm_wgrad_norm"):
+            fn = getattr(lib, name)
+            fn.restype = ci
+            fn.argtypes = [ctypes.POINTER(_PlanC), ctypes.POINTER(_QTensorC), ctypes.POINTER(_QTensorC),
+                           vp, i64, ci, vp, vp, sz, vp]
+        lib.snip_loss_divergence.restype = ctypes.c_double
+        lib.snip_loss_divergence.argtypes = [ctypes.c_double, ctypes.c_double, i64, ctypes.c_double, ctypes.c_double, i64, i64]
         lib.snip_quant_error_stats.restype = ci
         lib.snip_quant_error_stats.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, vp, sz, vp]
         lib.snip_status_string.restype = ctypes.c_char_p
@@ -181,6 +192,49 @@ def _gemm(fn_name: str, plan, a: QTensor, b: QTensor, out, out_dtype, stream):
     _check(getattr(_lib(), fn_name)(ctypes.byref(plan), ctypes.byref(qa), ctypes.byref(qb), out.data_ptr(),
                                     out.stride(0), out_dtype, None, 0, _stream(stream)), fn_name)
     return out
+
+
+def gemm_workspace_bytes(out_rows: int, out_cols: int) -> int:
+    return int(_lib().snip_gemm_workspace_bytes(out_rows, out_cols))
+
+
+def _gemm_norm(fn_name, plan, a: QTensor, b: QTensor, out, out_dtype, sum_sq, workspace, stream):
+    if not isinstance(plan, _PlanC):
+        plan = make_plan(plan)
+    dt = torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32
+    if out is None:
+        out = torch.empty((a.rows, b.rows), dtype=dt, device=a.codes.device)
+    if sum_sq is None:
+        sum_sq = torch.empty(1, dtype=torch.float64, device=a.codes.device)
+    if workspace is None:
+        workspace = torch.empty(gemm_workspace_bytes(a.rows, b.rows), dtype=torch.uint8, device=a.codes.device)
+    qa, qb = a.c_struct(), b.c_struct()
+    _check(getattr(_lib(), fn_name)(ctypes.byref(plan), ctypes.byref(qa), ctypes.byref(qb),
+                                    out.data_ptr(), out.stride(0), out_dtype, sum_sq.data_ptr(), workspace.data_ptr(),
+                                    workspace.numel(), _stream(stream)), fn_name)
+    return out, sum_sq
+
+
+def snip_gemm_fwd_norm(plan, xq_row: QTensor, wq_row: QTensor, out=None, out_dtype=OUT_BF16, sum_sq=None,
+                       workspace=None, stream=None):
+    """snip_gemm_fwd plus the squared Frobenius norm of Y as stored; returns (Y, sum_sq float64[1])."""
+    return _gemm_norm("snip_gemm_fwd_norm", plan, xq_row, wq_row, out, out_dtype, sum_sq, workspace, stream)
+
+
+def snip_gemm_dgrad_norm(plan, dyq_row: QTensor, wq_col: QTensor, out=None, out_dtype=OUT_BF16, sum_sq=None,
+                         workspace=None, stream=None):
+    return _gemm_norm("snip_gemm_dgrad_norm", plan, dyq_row, wq_col, out, out_dtype, sum_sq, workspace, stream)
+
+
+def snip_gemm_wgrad_norm(plan, dyq_col: QTensor, xq_col: QTensor, out=None, out_dtype=OUT_BF16, sum_sq=None,
+                         workspace=None, stream=None):
+    return _gemm_norm("snip_gemm_wgrad_norm", plan, dyq_col, xq_col, out, out_dtype, sum_sq, workspace, stream)
+
+
+def snip_loss_divergence(grad_x_sq: float, err_x_sq: float, m: int, grad_w_sq: float, err_w_sq: float,
+                         n: int, k: int) -> float:
+    return float(_lib().snip_loss_divergence(float(grad_x_sq), float(err_x_sq), m, float(grad_w_sq),
+                                             float(err_w_sq), n, k))
 
 
 def snip_gemm_fwd(plan, xq_row: QTensor, wq_row: QTensor, out=None, out_dtype=OUT_BF16, stream=None):

@@ -64,6 +64,42 @@ def test_validation_rejects_before_launch():
     assert L.snip_status_string(4).decode().startswith("bad alignment")
 
 
+def test_gemm_norm_validation_and_workspace_size():
+    snip = lib()
+    L = snip._lib()
+    fake = ctypes.c_void_p(0x1000)
+    assert snip.gemm_workspace_bytes(256, 256) >= 4 * 4            # four 128 x 128 tiles, one float each
+    assert snip.gemm_workspace_bytes(100, 100) >= 4
+    assert snip.gemm_workspace_bytes(16384, 11008) >= 128 * 86 * 4
+    assert snip.gemm_workspace_bytes(-1, 5) == 0
+    plan = snip.make_plan((0,) * 6)
+    qa = snip._QTensorC(0x1000, 0x2000, 0, 64, 64, 0)
+    qb = snip._QTensorC(0x3000, 0x4000, 0, 32, 64, 0)
+    args = (ctypes.byref(plan), ctypes.byref(qa), ctypes.byref(qb), fake, 32, 0)
+    assert L.snip_gemm_fwd_norm(*args, None, fake, 1 << 20, None) == 1      # no place for the norm
+    assert L.snip_gemm_dgrad_norm(*args, fake, None, 0, None) == 5          # workspace missing
+    assert L.snip_gemm_wgrad_norm(*args, fake, fake, 8, None) == 5          # workspace too small
+
+
+def test_loss_divergence_host_function_against_oracle():
+    """Pure host arithmetic: checked here without a GPU, to 1e-14 (the two sides group the square roots
+    differently)."""
+    import math
+    import numpy as np
+    import oracle
+    snip = lib()
+    rng = np.random.default_rng(60)
+    for _ in range(200):
+        gx, ex, gw, ew = (float(v) for v in 10.0 ** rng.uniform(-12, 12, size=4))
+        m, n, k = (int(v) for v in rng.integers(1, 1 << 20, size=3))
+        want = oracle.loss_divergence(gx, ex, m, gw, ew, n, k)
+        assert math.isclose(snip.snip_loss_divergence(gx, ex, m, gw, ew, n, k), want, rel_tol=1e-14)
+    assert snip.snip_loss_divergence(36.0, 36.0, 16, 16.0, 36.0, 4, 9) == 5.0
+    assert snip.snip_loss_divergence(0.0, 0.0, 1, 0.0, 0.0, 1, 1) == 0.0
+    assert math.isnan(snip.snip_loss_divergence(1.0, 1.0, 0, 1.0, 1.0, 4, 4))
+    assert math.isnan(snip.snip_loss_divergence(-1.0, 1.0, 4, 1.0, 1.0, 4, 4))
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     from paper_2602_01410_amd import snip
     monkeypatch.setattr(snip, "_handle", None)

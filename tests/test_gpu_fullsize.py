@@ -82,6 +82,17 @@ def test_linear_at_full_size(config, plan_name, linear):
     assert np.linalg.norm(got - want) <= TOL * np.linalg.norm(want)
     del Xh_col
 
+    # ---- norm-returning variants: same stored output bit for bit; the norm is that of the stored output,
+    #      and on the sampled rows the stored squares agree with the oracle's rounded product ----
+    dx2, ndx = snip.snip_gemm_dgrad_norm(plan, dyq_r, wq_c)
+    dw2, ndw = snip.snip_gemm_wgrad_norm(plan, dyq_c, xq_c)
+    torch.cuda.synchronize()
+    assert torch.equal(dx2, dx) and torch.equal(dw2, dw)
+    for out, n in ((dx, ndx), (dw, ndw)):
+        stored = float((out.double() ** 2).sum())
+        assert float(host(n)[0]) == pytest.approx(stored, rel=5e-6)
+    assert float((dw[ns].double() ** 2).sum()) == pytest.approx(oracle.output_sum_sq(want), rel=1e-4)
+
     # ---- statistics: sampled lines against the oracle, and total = sum of lines ----
     for t_dev, t_host, axis, idx in ((ddY, dY, snip.ROW, ms), (dX_, X, snip.COL, ks)):
         L = t_host.shape[0] if axis == snip.ROW else t_host.shape[1]
