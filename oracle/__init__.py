@@ -68,6 +68,15 @@ def _load():
             fn.argtypes = [vp, vp, i64, i64, i64, vp]
         lib.oracle_stats.restype = ci
         lib.oracle_stats.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp]
+        u32p = ctypes.POINTER(ctypes.c_uint32)
+        lib.oracle_threefry2x32_20.restype = None
+        lib.oracle_threefry2x32_20.argtypes = [u32p, u32p, u32p]
+        lib.oracle_sr_byte.restype = ctypes.c_uint
+        lib.oracle_sr_byte.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+        lib.oracle_encode_sr_fp4.restype = ctypes.c_uint
+        lib.oracle_encode_sr_fp4.argtypes = [dbl, ctypes.c_uint]
+        lib.oracle_quantize_sr_fp4.restype = ci
+        lib.oracle_quantize_sr_fp4.argtypes = [vp, i64, i64, i64, ci, ci, ctypes.c_uint64, vp, vp]
         lib.oracle_round_output.restype = dbl
         lib.oracle_round_output.argtypes = [dbl, ci]
         lib.oracle_output_sum_sq.restype = dbl
@@ -235,3 +244,33 @@ def loss_divergence(grad_x_sq: float, err_x_sq: float, M: int, grad_w_sq: float,
     """Loss-divergence estimate of one linear layer from squared Frobenius norms."""
     return float(_load().oracle_loss_divergence(float(grad_x_sq), float(err_x_sq), M,
                                                 float(grad_w_sq), float(err_w_sq), N, K))
+
+
+def threefry2x32_20(ctr, key):
+    """Threefry-2x32, 20 rounds: (c0, c1), (k0, k1) -> (x0, x1), all 32-bit."""
+    A = ctypes.c_uint32 * 2
+    c, k, o = A(*[int(v) & 0xFFFFFFFF for v in ctr]), A(*[int(v) & 0xFFFFFFFF for v in key]), A()
+    _load().oracle_threefry2x32_20(c, k, o)
+    return int(o[0]), int(o[1])
+
+
+def sr_byte(seed: int, index: int) -> int:
+    """Random byte of stored element `index` under `seed`."""
+    return int(_load().oracle_sr_byte(int(seed) & (2 ** 64 - 1), int(index)))
+
+
+def encode_sr_fp4(v: float, rnd: int) -> int:
+    """FP4 code of v (already divided by the block scale) under stochastic rounding with random byte rnd."""
+    return int(_load().oracle_encode_sr_fp4(float(v), int(rnd)))
+
+
+def quantize_sr_fp4(x_bf16_bits, axis: int = ROW, rule: int = NO_OVERFLOW, seed: int = 0):
+    """(codes uint8 [SR, SC/2], scales uint8 [SR, SC/32]) with stochastically rounded FP4 elements."""
+    x = _bf16_2d(x_bf16_bits)
+    rows, cols = x.shape
+    sr, sc = stored_shape(rows, cols, axis)
+    codes = np.zeros((sr, sc // 2), dtype=np.uint8)
+    scales = np.zeros((sr, sc // TILE), dtype=np.uint8)
+    _check(_load().oracle_quantize_sr_fp4(_ptr(x), rows, cols, cols, axis, rule, int(seed) & (2 ** 64 - 1),
+                                          _ptr(codes), _ptr(scales)), "quantize_sr_fp4")
+    return codes, scales

@@ -381,3 +381,107 @@ double oracle_loss_divergence(double grad_x_sq, double err_x_sq, int64_t M,
     double tw = sqrt(grad_w_sq) * sqrt(err_w_sq) / sqrt((double)N * (double)K);
     return sqrt(tx * tx + tw * tw);
 }
+
+/* ---- stochastic rounding of FP4 output gradients (Sec. 5.1 "Quantization Format and
+ *      Implementation": values are rounded probabilistically to the two nearest values) ---- */
+
+/* Threefry-2x32 with 20 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+ * as 1, 2, 3", SC'11): a counter-based generator, out = f(counter, key).  Written out from the
+ * published description: the key is extended by a third word (XOR of the key words with the
+ * parity constant 0x1BD11BDA); a round adds word 1 into word 0, rotates word 1 left by the
+ * round's constant and XORs word 0 into it; after every fourth round the next two key words
+ * (cyclically) are added, the second one together with the injection number. */
+static uint32_t rotl32(uint32_t v, int r) { return (v << r) | (v >> (32 - r)); }
+
+void oracle_threefry2x32_20(const uint32_t ctr[2], const uint32_t key[2], uint32_t out[2])
+{
+    static const int rot[8] = { 13, 15, 26, 6, 17, 29, 16, 24 };
+    uint32_t ks[3] = { key[0], key[1], 0x1BD11BDAu ^ key[0] ^ key[1] };
+    uint32_t x0 = ctr[0] + ks[0], x1 = ctr[1] + ks[1];
+    for (int round = 0; round < 20; ++round) {
+        x0 += x1;
+        x1 = rotl32(x1, rot[round % 8]);
+        x1 ^= x0;
+        if (round % 4 == 3) {
+            int inj = round / 4 + 1;                 /* 1 .. 5 */
+            x0 += ks[inj % 3];
+            x1 += ks[(inj + 1) % 3] + (uint32_t)inj;
+        }
+    }
+    out[0] = x0; out[1] = x1;
+}
+
+/* The random byte of stored element number `index` (row-major position in the STORED matrix)
+ * under `seed`: elements are served in groups of eight by one generator call with counter =
+ * index / 8 (low word first) and key = seed (low word first); element j of a group takes
+ * byte j of the 64 output bits, word 0 first, least significant byte first. */
+unsigned oracle_sr_byte(uint64_t seed, uint64_t index)
+{
+    uint64_t group = index / 8;
+    uint32_t ctr[2] = { (uint32_t)group, (uint32_t)(group >> 32) };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[2];
+    oracle_threefry2x32_20(ctr, key, out);
+    unsigned j = (unsigned)(index % 8);
+    return (out[j / 4] >> (8 * (j % 4))) & 0xFFu;
+}
+
+/* Stochastic rounding of v (already divided by the block scale) onto the FP4 E2M1 grid with
+ * the random byte rnd (0..255).  lo <= |v| <= hi are the two nearest grid magnitudes; the
+ * magnitude goes up to hi with probability p = (|v| - lo) / (hi - lo), realised as
+ *     up  <=>  rnd < floor(256 p).
+ * Grid values stay where they are for every rnd; magnitudes at or beyond the largest grid
+ * value give the largest code (they only occur under the saturating scale rule); the sign is
+ * kept (so a negative value that rounds to zero gives the code of -0).  Returns the 4-bit code. */
+unsigned oracle_encode_sr_fp4(double v, unsigned rnd)
+{
+    unsigned sign = signbit(v) ? 8u : 0u;
+    double a = fabs(v);
+    if (isnan(a)) return sign;           /* not produced by the path: blocks with NaN/Inf get zero codes */
+    unsigned top = fmt_max_code(1);
+    if (a >= oracle_decode(1, top)) return sign | top;
+    unsigned lo_code = 0;
+    while (oracle_decode(1, lo_code + 1) <= a) ++lo_code;        /* largest grid magnitude <= a */
+    double lo = oracle_decode(1, lo_code), hi = oracle_decode(1, lo_code + 1);
+    double p = (a - lo) / (hi - lo);                             /* exact: hi - lo is a power of two */
+    double threshold = floor(256.0 * p);
+    return sign | (lo_code + ((double)rnd < threshold ? 1u : 0u));
+}
+
+/* Quantize a bf16 matrix to FP4 with stochastic rounding.  Layout, scale rule, axis and the
+ * treatment of zero and non-finite blocks are those of oracle_quantize (the scale does not
+ * depend on the rounding mode); fmt is fixed to FP4. */
+int oracle_quantize_sr_fp4(const uint16_t* src, int64_t rows, int64_t cols, int64_t ld,
+                           int axis, int rule, uint64_t seed, uint8_t* codes, uint8_t* scales)
+{
+    if (!src || !codes || !scales) return -1;
+    if ((axis != 0 && axis != 1) || (rule != 0 && rule != 1)) return -1;
+    if (rows < 0 || cols < 0 || ld < cols) return -1;
+    const int64_t SR = axis == 0 ? rows : cols;
+    const int64_t SC = axis == 0 ? cols : rows;
+    if (SC % ORACLE_TILE) return -1;
+    const int64_t nb = SC / ORACLE_TILE;
+    memset(codes, 0, (size_t)(SR * SC / 2));
+    for (int64_t r = 0; r < SR; ++r)
+        for (int64_t b = 0; b < nb; ++b) {
+            double amax = 0.0;
+            int bad = 0;
+            for (int k = 0; k < ORACLE_TILE; ++k) {
+                double x = oracle_bf16_to_f64(stored_elem(src, ld, axis, r, b * ORACLE_TILE + k));
+                if (isnan(x) || isinf(x)) bad = 1;
+                else if (fabs(x) > amax) amax = fabs(x);
+            }
+            unsigned byte = bad ? 0xFFu : oracle_scale_byte(1, rule, amax);
+            scales[r * nb + b] = (uint8_t)byte;
+            if (bad) continue;                                   /* codes stay zero */
+            double scale = ldexp(1.0, (int)byte - 127);
+            for (int k = 0; k < ORACLE_TILE; ++k) {
+                int64_t c = b * ORACLE_TILE + k;
+                double x = oracle_bf16_to_f64(stored_elem(src, ld, axis, r, c));
+                uint64_t index = (uint64_t)r * (uint64_t)SC + (uint64_t)c;
+                unsigned code = oracle_encode_sr_fp4(x / scale, oracle_sr_byte(seed, index));
+                codes[(r * SC + c) / 2] |= (uint8_t)(code << (4 * (c % 2)));
+            }
+        }
+    return 0;
+}
