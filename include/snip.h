@@ -132,6 +132,22 @@ snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
                           const snip_qtensor* out, snip_stats* stats,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* Quantize to FP4 with stochastic rounding (Sec. 5.1 "Quantization Format and Implementation":
+ * FP4 output gradients are rounded probabilistically to the two nearest values).  Arguments,
+ * layout, scales (bit-identical to snip_quantize with SNIP_FP4_E2M1) and error behaviour as for
+ * snip_quantize; out->fmt must be SNIP_FP4_E2M1.  The rounding is a pure function of (x, seed):
+ *   - element i (row-major position in the STORED matrix) draws the random byte rnd = byte
+ *     (i mod 8) of the 64 bits Threefry-2x32-20(counter = i div 8, key = seed) (Salmon et al.,
+ *     SC'11; counter and key low word first; output word 0 first, least significant byte first);
+ *   - with lo <= |v| <= hi the grid magnitudes next to the scaled element v and
+ *     p = (|v| - lo) / (hi - lo), the magnitude becomes hi iff rnd < floor(256 p), else lo.
+ * Grid values are kept for every seed; the expectation over rnd equals v exactly for
+ * |v| >= 0.25 (p then has at most 8 bits) and lies within 0.5/256 below |v| otherwise.
+ * Use a fresh seed per tensor and step. */
+snip_status snip_quantize_sr_fp4(const void* x, int64_t rows, int64_t cols, int64_t ld,
+                                 snip_axis axis, snip_scale_rule rule, uint64_t seed,
+                                 const snip_qtensor* out, void* stream);
+
 /* ---- the three GEMMs (Sec. 2.2; shapes Sec. 4.1 / 4.3.1) ----------------------------- */
 /* All three contract the stored `cols` of both operands: C[i][j] = sum_r A[i][r] * B[j][r]
  * with a = code * 2^(scale-127), accumulated in fp32 and rounded once (nearest even) to the

@@ -129,6 +129,28 @@ snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
     return launch_quantize(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
 }
 
+snip_status snip_quantize_sr_fp4(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_axis axis,
+                                 snip_scale_rule rule, uint64_t seed, const snip_qtensor* out, void* stream)
+{
+    snip_status st = check_source(x, rows, cols, ld, axis, rule);
+    if (st != SNIP_OK) return st;
+    if (!out) return SNIP_ERR_NULL;
+    if ((!out->codes || !out->scales) && rows > 0 && cols > 0) return SNIP_ERR_NULL;
+    if (out->fmt != (int32_t)SNIP_FP4_E2M1) return SNIP_ERR_FORMAT;
+    const int64_t sr = axis == SNIP_AXIS_ROW ? rows : cols, sc = axis == SNIP_AXIS_ROW ? cols : rows;
+    if (out->rows != sr || out->cols != sc) return SNIP_ERR_SHAPE;
+    if (!aligned16(out->codes)) return SNIP_ERR_LAYOUT;
+    if (out->scales_g4 && (reinterpret_cast<uintptr_t>(out->scales_g4) & 3u)) return SNIP_ERR_LAYOUT;
+    if (reinterpret_cast<uintptr_t>(out->scales) & 3u) return SNIP_ERR_LAYOUT;
+    QuantArgs a;
+    a.x = (const uint16_t*)x; a.rows = rows; a.cols = cols; a.ld = ld;
+    a.fmt = SNIP_FP4_E2M1; a.axis = axis; a.rule = rule;
+    a.codes = (uint8_t*)out->codes; a.scales = out->scales; a.scales_g4 = out->scales_g4;
+    a.stats = nullptr; a.workspace = nullptr;
+    a.stochastic = true; a.sr_seed = seed;
+    return launch_quantize(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
+}
+
 snip_status snip_gemm_fwd(const snip_layer_plan* plan, const snip_qtensor* xq_row, const snip_qtensor* wq_row,
                           void* y, int64_t ld_out, snip_out_dtype out_dtype, void*, size_t, void* stream)
 {

@@ -101,6 +101,73 @@ __device__ __forceinline__ unsigned enc4(unsigned w0, unsigned w1, unsigned w2, 
     return r;
 }
 
+// ---- stochastic rounding to FP4 (Sec. 5.1: FP4 output gradients are rounded probabilistically to the two
+//      nearest values).  Definition: with lo <= |v| <= hi the neighbouring grid magnitudes of the scaled
+//      element and p = (|v| - lo) / (hi - lo), the magnitude goes up iff rnd < floor(256 p), rnd being the
+//      element's random byte: byte (i mod 8) of Threefry-2x32-20(counter = i div 8, key = seed), i the
+//      element's row-major position in the stored matrix. ----
+
+// Threefry-2x32, 20 rounds (Salmon et al., SC'11): adds, rotates and XORs only, which suits a VALU whose
+// 32-bit multiplies run at quarter rate.
+__device__ __forceinline__ unsigned rotl32(unsigned v, int r) { return (v << r) | (v >> (32 - r)); }
+__device__ __forceinline__ void threefry2x32_20(unsigned c0, unsigned c1, unsigned k0, unsigned k1,
+                                                unsigned& o0, unsigned& o1)
+{
+    constexpr int R[8] = {13, 15, 26, 6, 17, 29, 16, 24};
+    const unsigned ks[3] = {k0, k1, 0x1BD11BDAu ^ k0 ^ k1};
+    unsigned x0 = c0 + ks[0], x1 = c1 + ks[1];
+#pragma unroll
+    for (int r = 0; r < 20; ++r) {
+        x0 += x1;
+        x1 = rotl32(x1, R[r % 8]) ^ x0;
+        if (r % 4 == 3) {
+            const int inj = r / 4 + 1;
+            x0 += ks[inj % 3];
+            x1 += ks[(inj + 1) % 3] + (unsigned)inj;
+        }
+    }
+    o0 = x0; o1 = x1;
+}
+
+// One element: bf16 value in the upper half of `fbits`, scale byte, random byte -> 4-bit code.
+// The grid spacing is 0.5 below 2, 1 in [2, 4) and 2 from 4 on, so with Ec = clamp(exponent of |v|, 0, 2)
+// and k = floor(|v| * 2^(9 - Ec)) the lower neighbour has code (k >> 8) + 2 Ec and floor(256 p) = k & 255.
+// v_ldexp_f32 scales exactly; a scaled magnitude too small for fp32 gives k = 0 like the exact value.
+__device__ __forceinline__ unsigned sr_code(unsigned fbits, unsigned byte, unsigned rnd)
+{
+    const int ex = (int)((fbits >> 23) & 0xFFu) - (int)byte;           // exponent of |v| (garbage-free: clamped next)
+    const int ec = ex < 0 ? 0 : (ex > 2 ? 2 : ex);
+    const float a = __builtin_ldexpf(__uint_as_float(fbits & 0x7FFFFFFFu), 136 - (int)byte - ec);
+    const unsigned k = (unsigned)a;                                     // truncation; |v| < 8 keeps k < 1024
+    unsigned code = (k >> 8) + 2u * (unsigned)ec + (rnd < (k & 0xFFu) ? 1u : 0u);
+    code = code > 7u ? 7u : code;
+    return code | ((fbits >> 28) & 8u);
+}
+
+// Four bf16 pairs (8 consecutive stored elements) -> 8 FP4 nibbles with stochastic rounding; r0 holds
+// the random bytes of elements 0-3, r1 those of elements 4-7.
+__device__ __forceinline__ unsigned enc4_sr(const unsigned* w, unsigned byte, unsigned r0, unsigned r1)
+{
+    unsigned out = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const unsigned rr = i < 2 ? r0 : r1;
+        const unsigned lo = sr_code(w[i] << 16, byte, (rr >> (16 * (i & 1))) & 0xFFu);
+        const unsigned hi = sr_code(w[i] & 0xFFFF0000u, byte, (rr >> (16 * (i & 1) + 8)) & 0xFFu);
+        out |= (lo | (hi << 4)) << (8 * i);
+    }
+    return out;
+}
+
+// Codes of the 8 consecutive stored elements that start at stored position e0 (a multiple of 8).
+__device__ __forceinline__ unsigned enc4_sr_at(const unsigned* w, unsigned byte, int64_t e0, uint2 seed)
+{
+    const uint64_t grp = (uint64_t)e0 >> 3;
+    unsigned r0, r1;
+    threefry2x32_20((unsigned)grp, (unsigned)(grp >> 32), seed.x, seed.y, r0, r1);
+    return enc4_sr(w, byte, r0, r1);
+}
+
 __device__ __forceinline__ void acc_err(float2_t q, unsigned w, float& s0, float& se, bool want_s0)
 {
     const float xl = __uint_as_float(w << 16), xh = __uint_as_float(w & 0xFFFF0000u);
@@ -146,14 +213,15 @@ __device__ __forceinline__ unsigned amax8(const uint4& v)
 constexpr int kSeg = 512;
 constexpr int kUnroll = 4;
 
-template <int FMT, int RULE, bool STATS>
+template <int FMT, int RULE, bool STATS, bool SR = false>
 __global__ __launch_bounds__(256) void quant_row_kernel(const uint16_t* __restrict__ x, int rows,
                                                         int cols, int64_t ld,
                                                         uint8_t* __restrict__ codes,
                                                         uint8_t* __restrict__ scales,
                                                         uint8_t* __restrict__ scales_g4, int64_t kpitch,
-                                                        float* __restrict__ partials)
+                                                        float* __restrict__ partials, uint2 seed)
 {
+    static_assert(!SR || (FMT == kFP4 && !STATS), "stochastic rounding: FP4, no fused statistics");
     // unit = (group of 4 consecutive rows, 512-element segment); the wave's four loads in flight
     // are the four rows, so that the block-major scale copy gets one dword (4 rows) per block.
     const int lane = threadIdx.x & 63;
@@ -192,7 +260,7 @@ __global__ __launch_bounds__(256) void quant_row_kernel(const uint16_t* __restri
                 if (act[j]) *reinterpret_cast<uint2*>(codes + e0) = make_uint2(c0, c1);
                 if (STATS) err8(w, c0, c1, sc, s0, se, true);
             } else {
-                unsigned c = enc4(w[0], w[1], w[2], w[3], sc);
+                unsigned c = SR ? enc4_sr_at(w, byte, e0, seed) : enc4(w[0], w[1], w[2], w[3], sc);
                 if (bad) c = 0;
                 if (act[j]) *reinterpret_cast<unsigned*>(codes + (e0 >> 1)) = c;
                 if (STATS) err4(w, c, sc, s0, se, true);
@@ -308,9 +376,10 @@ __device__ __forceinline__ void load_col_block(const uint16_t* __restrict__ p, i
 // Codes of one column's block (32 rows) -> the wave's LDS staging area; returns the scale byte.
 // In LDS the wave keeps a [128 stored rows][ROWB bytes] image of its unit's output (ROWB = 128 FP8,
 // 64 FP4 bytes = 128 source rows); 16-byte chunk c of row r sits at position c ^ ((r >> 1) & (CPR-1)).
-template <int FMT, int RULE, bool STATS>
+template <int FMT, int RULE, bool STATS, bool SR>
 __device__ __forceinline__ unsigned quant_one_column(const unsigned* w, unsigned am, uint8_t* __restrict__ lds_row,
-                                                     int rb_local, int swz, float& s0, float& se)
+                                                     int rb_local, int swz, float& s0, float& se,
+                                                     int64_t e0, uint2 seed)      // e0: stored position of w[0]'s first element
 {
     const unsigned byte = scale_byte<FMT, RULE>(am);
     const float sc = scale_operand(byte);
@@ -332,7 +401,8 @@ __device__ __forceinline__ unsigned quant_one_column(const unsigned* w, unsigned
         unsigned c[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            c[k] = enc4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3], sc);
+            c[k] = SR ? enc4_sr_at(w + 4 * k, byte, e0 + 8 * k, seed)
+                      : enc4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3], sc);
             if (bad) c[k] = 0;
         }
         *reinterpret_cast<uint4*>(lds_row + ((rb_local ^ swz) * 16)) = make_uint4(c[0], c[1], c[2], c[3]);
@@ -344,14 +414,15 @@ __device__ __forceinline__ unsigned quant_one_column(const unsigned* w, unsigned
     return byte;
 }
 
-template <int FMT, int RULE, bool STATS>
+template <int FMT, int RULE, bool STATS, bool SR = false>
 __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restrict__ x, int rows,
                                                         int cols, int64_t ld,
                                                         uint8_t* __restrict__ codes,
                                                         uint8_t* __restrict__ scales,
                                                         uint8_t* __restrict__ scales_g4, int64_t kpitch,
-                                                        float* __restrict__ partials)
+                                                        float* __restrict__ partials, uint2 seed)
 {
+    static_assert(!SR || (FMT == kFP4 && !STATS), "stochastic rounding: FP4, no fused statistics");
     constexpr int ROWB = FMT == kFP8 ? 128 : 64;     // staged output bytes per stored row (128 source rows)
     constexpr int CPR = ROWB / 16;
     __shared__ __attribute__((aligned(16))) uint8_t stage[kWavesPerBlock][kColsPerWave * ROWB];
@@ -376,8 +447,9 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
         for (int k = 0; k < nb; ++k) {
             ColBlock b;
             load_col_block(x + (int64_t)(rb0 + k) * kBlock * ld + c, ld, act, b);
-            const unsigned y0 = quant_one_column<FMT, RULE, STATS>(b.lo, b.am_lo, reg + (2 * lane) * ROWB, k, swz_lo, s0, se);
-            const unsigned y1 = quant_one_column<FMT, RULE, STATS>(b.hi, b.am_hi, reg + (2 * lane + 1) * ROWB, k, swz_lo, s0, se);
+            const int64_t e0 = (int64_t)c * rows + (int64_t)(rb0 + k) * kBlock;       // stored row = source column
+            const unsigned y0 = quant_one_column<FMT, RULE, STATS, SR>(b.lo, b.am_lo, reg + (2 * lane) * ROWB, k, swz_lo, s0, se, e0, seed);
+            const unsigned y1 = quant_one_column<FMT, RULE, STATS, SR>(b.hi, b.am_hi, reg + (2 * lane + 1) * ROWB, k, swz_lo, s0, se, e0 + rows, seed);
             g4_lo |= y0 << (8 * k);
             g4_hi |= y1 << (8 * k);
         }
@@ -541,18 +613,19 @@ size_t workspace_bytes(int64_t rows, int64_t cols)
     return kPartialBytes + (size_t)kMaxColSplits * (size_t)cols * 3 * sizeof(float);
 }
 
-template <int FMT, int RULE, bool STATS>
+template <int FMT, int RULE, bool STATS, bool SR = false>
 static void launch_q(const QuantArgs& a, float* partials, hipStream_t s)
 {
+    const uint2 seed = make_uint2((unsigned)a.sr_seed, (unsigned)(a.sr_seed >> 32));
     // pitch of the block-major scale copy = padded number of STORED rows
     if (a.axis == 0)
-        hipLaunchKernelGGL((quant_row_kernel<FMT, RULE, STATS>), dim3(kStreamBlocks), dim3(256), 0, s,
+        hipLaunchKernelGGL((quant_row_kernel<FMT, RULE, STATS, SR>), dim3(kStreamBlocks), dim3(256), 0, s,
                            a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, a.scales_g4,
-                           g4_pitch(a.rows), partials);
+                           g4_pitch(a.rows), partials, seed);
     else
-        hipLaunchKernelGGL((quant_col_kernel<FMT, RULE, STATS>), dim3(kStreamBlocks), dim3(256), 0, s,
+        hipLaunchKernelGGL((quant_col_kernel<FMT, RULE, STATS, SR>), dim3(kStreamBlocks), dim3(256), 0, s,
                            a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, a.scales_g4,
-                           g4_pitch(a.cols), partials);
+                           g4_pitch(a.cols), partials, seed);
 }
 
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
@@ -566,6 +639,12 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
     }
     float* partials = (float*)a.workspace;
     const bool st = a.stats != nullptr;
+    if (a.stochastic) {
+        if (a.fmt != kFP4 || st) return hipErrorInvalidValue;
+        if (a.rule == 0) launch_q<kFP4, 0, false, true>(a, partials, s);
+        else             launch_q<kFP4, 1, false, true>(a, partials, s);
+        return hipGetLastError();
+    }
     const int key = (a.fmt << 2) | (a.rule << 1) | (st ? 1 : 0);
     switch (key) {
         case 0: launch_q<kFP8, 0, false>(a, partials, s); break;

@@ -30,6 +30,8 @@ struct QuantArgs {
     uint8_t* scales_g4;       // [ceil(stored cols / 128)][g4_pitch(stored rows)][4] or nullptr
     double* stats;        // device snip_stats (3 doubles) or nullptr
     void* workspace;
+    bool stochastic = false;  // FP4 only: stochastic rounding with the byte stream of sr_seed
+    uint64_t sr_seed = 0;
 };
 
 struct StatsArgs {

@@ -26,7 +26,7 @@ EXPORTS = ("snip_qtensor_code_bytes", "snip_qtensor_scale_bytes", "snip_qtensor_
            "snip_quantize", "snip_gemm_fwd", "snip_gemm_dgrad", "snip_gemm_wgrad",
            "snip_quant_error_stats", "snip_status_string",
            "snip_gemm_workspace_bytes", "snip_gemm_fwd_norm", "snip_gemm_dgrad_norm", "snip_gemm_wgrad_norm",
-           "snip_loss_divergence")
+           "snip_loss_divergence", "snip_quantize_sr_fp4")
 
 
 class SnipError(RuntimeError):
@@ -73,6 +73,8 @@ def _lib():
             fn.restype = ci
             fn.argtypes = [ctypes.POINTER(_PlanC), ctypes.POINTER(_QTensorC), ctypes.POINTER(_QTensorC),
                            vp, i64, ci, vp, sz, vp]
+        lib.snip_quantize_sr_fp4.restype = ci
+        lib.snip_quantize_sr_fp4.argtypes = [vp, i64, i64, i64, ci, ci, ctypes.c_uint64, ctypes.POINTER(_QTensorC), vp]
         lib.snip_gemm_workspace_bytes.restype = sz
         lib.snip_gemm_workspace_bytes.argtypes = [i64, i64]
         for name in ("snip_gemm_fwd_norm", "snip_gemm_dgrad_norm", "snip_gemm_wgrad_norm"):
@@ -179,6 +181,19 @@ def snip_quantize(x: torch.Tensor, fmt: int, axis: int = ROW, rule: int = NO_OVE
                                 workspace.data_ptr() if workspace is not None else None,
                                 workspace.numel() if workspace is not None else 0, _stream(stream)),
            "snip_quantize")
+    return out
+
+
+def snip_quantize_sr_fp4(x: torch.Tensor, axis: int = ROW, rule: int = NO_OVERFLOW, seed: int = 0,
+                         out: Optional[QTensor] = None, stream=None) -> QTensor:
+    """FP4 quantization with stochastic rounding; `seed` (64 bit) selects the random byte stream."""
+    ptr, rows, cols, ld = _src(x)
+    if out is None:
+        sr, sc = (rows, cols) if axis == ROW else (cols, rows)
+        out = alloc_qtensor(sr, sc, FP4, x.device)
+    q = out.c_struct()
+    _check(_lib().snip_quantize_sr_fp4(ptr, rows, cols, ld, axis, rule, int(seed) & (2 ** 64 - 1), ctypes.byref(q),
+                                       _stream(stream)), "snip_quantize_sr_fp4")
     return out
 
 
