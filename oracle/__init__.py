@@ -77,6 +77,10 @@ def _load():
         lib.oracle_encode_sr_fp4.argtypes = [dbl, ctypes.c_uint]
         lib.oracle_quantize_sr_fp4.restype = ci
         lib.oracle_quantize_sr_fp4.argtypes = [vp, i64, i64, i64, ci, ci, ctypes.c_uint64, vp, vp]
+        lib.oracle_adamw_sensitivity_sq.restype = dbl
+        lib.oracle_adamw_sensitivity_sq.argtypes = [vp, vp, vp, i64, dbl, dbl, dbl]
+        lib.oracle_weight_divergence.restype = dbl
+        lib.oracle_weight_divergence.argtypes = [dbl, dbl, dbl, i64, dbl, dbl, i64, i64]
         lib.oracle_round_output.restype = dbl
         lib.oracle_round_output.argtypes = [dbl, ci]
         lib.oracle_output_sum_sq.restype = dbl
@@ -274,3 +278,17 @@ def quantize_sr_fp4(x_bf16_bits, axis: int = ROW, rule: int = NO_OVERFLOW, seed:
     _check(_load().oracle_quantize_sr_fp4(_ptr(x), rows, cols, cols, axis, rule, int(seed) & (2 ** 64 - 1),
                                           _ptr(codes), _ptr(scales)), "quantize_sr_fp4")
     return codes, scales
+
+
+def adamw_sensitivity_sq(m, v, g, beta1: float, beta2: float, eps: float) -> float:
+    """Squared Frobenius norm of dh/dg for the AdamW update direction h = m / (sqrt(v) + eps)."""
+    a = [np.ascontiguousarray(np.asarray(t, dtype=np.float64)).ravel() for t in (m, v, g)]
+    assert a[0].size == a[1].size == a[2].size
+    return float(_load().oracle_adamw_sensitivity_sq(_ptr(a[0]), _ptr(a[1]), _ptr(a[2]), a[0].size,
+                                                     float(beta1), float(beta2), float(eps)))
+
+
+def weight_divergence(alpha: float, beta1: float, beta2: float, t: int, sens_sq: float, err_g_sq: float,
+                      N: int, K: int) -> float:
+    return float(_load().oracle_weight_divergence(float(alpha), float(beta1), float(beta2), int(t),
+                                                  float(sens_sq), float(err_g_sq), N, K))

@@ -485,3 +485,36 @@ int oracle_quantize_sr_fp4(const uint16_t* src, int64_t rows, int64_t cols, int6
         }
     return 0;
 }
+
+/* ---- AdamW factor of the weight-divergence estimate (Sec. 4.3.2 "Impact on Weight Divergence") ---- */
+
+/* With m = beta1 m' + (1-beta1) g and v = beta2 v' + (1-beta2) g^2 the update direction
+ * h(g) = m / (sqrt(v) + eps) has the element-wise derivative
+ *     dh/dg = (1-beta1) / (sqrt(v)+eps)  -  (1-beta2) m g / ( sqrt(v) (sqrt(v)+eps)^2 ),
+ * and Step 1 collects the Frobenius norm of that term.  Returns its SQUARE, summed in index
+ * order in double.  Where v is zero the second part is taken as zero (AdamW has m = g = 0
+ * there; the expression itself would be 0/0). */
+double oracle_adamw_sensitivity_sq(const double* m, const double* v, const double* g, int64_t n,
+                                   double beta1, double beta2, double eps)
+{
+    double s = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double root = sqrt(v[i]);
+        double first = (1.0 - beta1) / (root + eps);
+        double second = 0.0;
+        if (v[i] > 0.0) second = (1.0 - beta2) * m[i] * g[i] / (root * (root + eps) * (root + eps));
+        double t = first - second;
+        s += t * t;
+    }
+    return s;
+}
+
+/* The per-layer weight-divergence estimate that the factor feeds (same section):
+ *     alpha * sqrt(1 - beta2^t) / (1 - beta1^t) * ||dh/dg||_F * ||eps_g||_F / sqrt(N K)
+ * from squared norms; eps_g is the perturbation of the weight gradient. */
+double oracle_weight_divergence(double alpha, double beta1, double beta2, int64_t t,
+                                double sens_sq, double err_g_sq, int64_t N, int64_t K)
+{
+    double corr = sqrt(1.0 - pow(beta2, (double)t)) / (1.0 - pow(beta1, (double)t));
+    return alpha * corr * sqrt(sens_sq) * sqrt(err_g_sq) / sqrt((double)N * (double)K);
+}
