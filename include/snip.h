@@ -205,6 +205,31 @@ snip_status snip_gemm_wgrad_norm(const snip_layer_plan* plan, const snip_qtensor
 double snip_loss_divergence(double grad_x_sq, double err_x_sq, int64_t m,
                             double grad_w_sq, double err_w_sq, int64_t n, int64_t k);
 
+/* ---- AdamW factor of the weight-divergence estimate (Sec. 4.3.2) ---------------------- */
+/* With m = beta1 m' + (1-beta1) g and v = beta2 v' + (1-beta2) g^2 (the AdamW moments after the
+ * step's update) the update direction h(g) = m / (sqrt(v) + eps) has the element-wise derivative
+ *     (1-beta1) / (sqrt(v)+eps)  -  (1-beta2) m g / ( sqrt(v) (sqrt(v)+eps)^2 );
+ * Step 1 collects the Frobenius norm of that term (Sec. 4.3.2 "Impact on Weight Divergence").
+ * This call writes its SQUARE to *sum_sq.
+ *   m, v : device, fp32 [n], 16-byte aligned.  Where v is zero the second part counts as zero.
+ *   g    : device, [n], fp32 (g_dtype = SNIP_OUT_FP32, 16-byte aligned) or bf16 (SNIP_OUT_BF16,
+ *          8-byte aligned; e.g. the dW a wgrad call produced).
+ *   beta1, beta2 in [0, 1), eps >= 0 (SNIP_ERR_FORMAT otherwise).
+ *   sum_sq: device, one double.  workspace: device, required, >= snip_workspace_bytes(0, 0).
+ * fp32 arithmetic with correctly rounded division and square root; fixed summation order. */
+snip_status snip_adamw_sensitivity(const float* m, const float* v, const void* g,
+                                   snip_out_dtype g_dtype, int64_t n, float beta1, float beta2,
+                                   float eps, double* sum_sq, void* workspace,
+                                   size_t workspace_bytes, void* stream);
+
+/* Host, pure.  The per-layer weight-divergence estimate the factor feeds (same section):
+ *     alpha sqrt(1 - beta2^t) / (1 - beta1^t) * sqrt(sens_sq) * sqrt(err_g_sq) / sqrt(n k)
+ * for a weight of n x k elements at optimizer step t >= 1; sens_sq from snip_adamw_sensitivity,
+ * err_g_sq the squared Frobenius norm of the perturbation of the weight gradient.  NaN on a
+ * bad argument. */
+double snip_weight_divergence(double alpha, double beta1, double beta2, int64_t t, double sens_sq,
+                              double err_g_sq, int64_t n, int64_t k);
+
 /* ---- quantization-error statistics (Sec. 3.1 Step 1; row-wise form: Sec. 5.3) -------- */
 
 /* One read of a bf16 matrix; for blocks along `axis` produces the squared Frobenius norm of x

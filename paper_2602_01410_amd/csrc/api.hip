@@ -213,6 +213,35 @@ double snip_loss_divergence(double grad_x_sq, double err_x_sq, int64_t m, double
     return std::hypot(tx, tw);
 }
 
+snip_status snip_adamw_sensitivity(const float* m, const float* v, const void* g, snip_out_dtype g_dtype,
+                                   int64_t n, float beta1, float beta2, float eps, double* sum_sq,
+                                   void* workspace, size_t workspace_bytes_, void* stream)
+{
+    if (n < 0) return SNIP_ERR_SHAPE;
+    if ((!m || !v || !g) && n > 0) return SNIP_ERR_NULL;
+    if (!sum_sq) return SNIP_ERR_NULL;
+    if (g_dtype != SNIP_OUT_BF16 && g_dtype != SNIP_OUT_FP32) return SNIP_ERR_FORMAT;
+    if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f)) return SNIP_ERR_FORMAT;
+    if (!aligned16(m) || !aligned16(v)) return SNIP_ERR_LAYOUT;
+    if (reinterpret_cast<uintptr_t>(g) & (g_dtype == SNIP_OUT_BF16 ? 7u : 15u)) return SNIP_ERR_LAYOUT;
+    if (!workspace || workspace_bytes_ < workspace_bytes(0, 0)) return SNIP_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SNIP_ERR_LAYOUT;
+    AdamwArgs a;
+    a.m = m; a.v = v; a.g = g; a.g_bf16 = g_dtype == SNIP_OUT_BF16; a.n = n;
+    a.beta1 = beta1; a.beta2 = beta2; a.eps = eps; a.out = sum_sq; a.workspace = workspace;
+    return launch_adamw_sensitivity(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
+}
+
+double snip_weight_divergence(double alpha, double beta1, double beta2, int64_t t, double sens_sq,
+                              double err_g_sq, int64_t n, int64_t k)
+{
+    if (t <= 0 || n <= 0 || k <= 0 || !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0) ||
+        !(sens_sq >= 0.0) || !(err_g_sq >= 0.0))
+        return std::nan("");
+    const double corr = std::sqrt(1.0 - std::pow(beta2, (double)t)) / (1.0 - std::pow(beta1, (double)t));
+    return alpha * corr * std::sqrt(sens_sq * err_g_sq / ((double)n * (double)k));
+}
+
 snip_status snip_quant_error_stats(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_axis axis,
                                    snip_scale_rule rule, snip_stats* out, float* per_line, void* workspace,
                                    size_t workspace_bytes_, void* stream)

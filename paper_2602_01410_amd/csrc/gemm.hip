@@ -304,6 +304,12 @@ __global__ __launch_bounds__(kNormThreads) void reduce_norm_kernel(const float* 
     if (threadIdx.x == 0) out[0] = sh[0];
 }
 
+hipError_t launch_sum_partials(const float* partials, int64_t n, double* out, hipStream_t s)
+{
+    hipLaunchKernelGGL(reduce_norm_kernel, dim3(1), dim3(kNormThreads), 0, s, partials, n, out);
+    return hipGetLastError();
+}
+
 static hipError_t launch_gemm_kernel(const GemmArgs& a, hipStream_t s)
 {
     if (gemm_fast_eligible(a)) return launch_gemm_fast(a, s);
@@ -325,8 +331,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
         if (!empty)
             n = gemm_fast_eligible(a) ? gemm_fast_partials(a)
                                       : ((a.I + BM - 1) / BM) * ((a.J + BN - 1) / BN);
-        hipLaunchKernelGGL(reduce_norm_kernel, dim3(1), dim3(kNormThreads), 0, s, (const float*)a.norm_partials, n, a.norm_out);
-        return hipGetLastError();
+        return launch_sum_partials(a.norm_partials, n, a.norm_out, s);
     }
     return hipSuccess;
 }

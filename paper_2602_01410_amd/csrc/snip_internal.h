@@ -56,7 +56,18 @@ struct GemmArgs {
 // Upper bound of the number of partials either GEMM kernel writes for an I x J output (128 x 128 tiles).
 inline int64_t gemm_norm_partials(int64_t I, int64_t J) { return ((I + 127) / 128) * ((J + 127) / 128); }
 
+struct AdamwArgs {
+    const float* m; const float* v; const void* g; int g_bf16;
+    int64_t n;
+    float beta1, beta2, eps;
+    double* out;          // device, one double
+    void* workspace;      // room for kStreamWaves floats
+};
+
 size_t workspace_bytes(int64_t rows, int64_t cols);
+hipError_t launch_adamw_sensitivity(const AdamwArgs& a, hipStream_t s);
+// out[0] = sum of partials[0..n) in index order, in double (one workgroup); n may be 0
+hipError_t launch_sum_partials(const float* partials, int64_t n, double* out, hipStream_t s);
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t s);
 hipError_t launch_stats(const StatsArgs& a, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);

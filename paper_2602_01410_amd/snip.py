@@ -26,7 +26,7 @@ EXPORTS = ("snip_qtensor_code_bytes", "snip_qtensor_scale_bytes", "snip_qtensor_
            "snip_quantize", "snip_gemm_fwd", "snip_gemm_dgrad", "snip_gemm_wgrad",
            "snip_quant_error_stats", "snip_status_string",
            "snip_gemm_workspace_bytes", "snip_gemm_fwd_norm", "snip_gemm_dgrad_norm", "snip_gemm_wgrad_norm",
-           "snip_loss_divergence", "snip_quantize_sr_fp4")
+           "snip_loss_divergence", "snip_quantize_sr_fp4", "snip_adamw_sensitivity", "snip_weight_divergence")
 
 
 class SnipError(RuntimeError):
@@ -75,6 +75,11 @@ def _lib():
                            vp, i64, ci, vp, sz, vp]
         lib.snip_quantize_sr_fp4.restype = ci
         lib.snip_quantize_sr_fp4.argtypes = [vp, i64, i64, i64, ci, ci, ctypes.c_uint64, ctypes.POINTER(_QTensorC), vp]
+        cf, cd = ctypes.c_float, ctypes.c_double
+        lib.snip_adamw_sensitivity.restype = ci
+        lib.snip_adamw_sensitivity.argtypes = [vp, vp, vp, ci, i64, cf, cf, cf, vp, vp, sz, vp]
+        lib.snip_weight_divergence.restype = cd
+        lib.snip_weight_divergence.argtypes = [cd, cd, cd, i64, cd, cd, i64, i64]
         lib.snip_gemm_workspace_bytes.restype = sz
         lib.snip_gemm_workspace_bytes.argtypes = [i64, i64]
         for name in ("snip_gemm_fwd_norm", "snip_gemm_dgrad_norm", "snip_gemm_wgrad_norm"):
@@ -195,6 +200,32 @@ def snip_quantize_sr_fp4(x: torch.Tensor, axis: int = ROW, rule: int = NO_OVERFL
     _check(_lib().snip_quantize_sr_fp4(ptr, rows, cols, ld, axis, rule, int(seed) & (2 ** 64 - 1), ctypes.byref(q),
                                        _stream(stream)), "snip_quantize_sr_fp4")
     return out
+
+
+def snip_adamw_sensitivity(m: torch.Tensor, v: torch.Tensor, g: torch.Tensor, beta1: float, beta2: float,
+                           eps: float, out: Optional[torch.Tensor] = None,
+                           workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Squared Frobenius norm of dh/dg of the AdamW update direction; m, v fp32, g fp32 or bf16, contiguous."""
+    assert m.dtype == torch.float32 and v.dtype == torch.float32 and g.dtype in (torch.float32, torch.bfloat16)
+    assert m.is_contiguous() and v.is_contiguous() and g.is_contiguous() and m.numel() == v.numel() == g.numel()
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=m.device)
+    if workspace is None:
+        workspace = alloc_workspace(0, 0, m.device)
+    n = m.numel()
+    _check(_lib().snip_adamw_sensitivity(m.data_ptr() if n else None, v.data_ptr() if n else None,
+                                         g.data_ptr() if n else None,
+                                         OUT_BF16 if g.dtype == torch.bfloat16 else OUT_FP32, n,
+                                         float(beta1), float(beta2), float(eps), out.data_ptr(),
+                                         workspace.data_ptr(), workspace.numel(), _stream(stream)),
+           "snip_adamw_sensitivity")
+    return out
+
+
+def snip_weight_divergence(alpha: float, beta1: float, beta2: float, t: int, sens_sq: float, err_g_sq: float,
+                           n: int, k: int) -> float:
+    return float(_lib().snip_weight_divergence(float(alpha), float(beta1), float(beta2), int(t), float(sens_sq),
+                                               float(err_g_sq), n, k))
 
 
 def _gemm(fn_name: str, plan, a: QTensor, b: QTensor, out, out_dtype, stream):

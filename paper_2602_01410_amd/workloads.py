@@ -168,6 +168,26 @@ def make_tensor(cfg: Config, kind: str, key: str, row_start: int = 0,
     raise KeyError(kind)
 
 
+def make_optimizer_state(cfg: Config, name: str, beta1: float = 0.9, beta2: float = 0.999):
+    """Synthetic AdamW state of one linear's weight after an update: (m, v, g) as float32 [N, K].
+
+    g ~ N(0, s) with s = dy_std * sqrt(M) (the scale of dW = dY^T X for unit-variance inputs); the previous
+    moments are those of a stationary run with the same gradient scale, m' ~ N(0, s sqrt((1-b1)/(1+b1))),
+    v' = s^2 (1 + 0.05 N(0,1)) kept positive; m and v are the moments after this step's update.  A recipe
+    for inputs only: it stands in for the optimizer state of the paper's training runs."""
+    idx = next(i for i, l in enumerate(cfg.linears) if l.name == name)
+    lin = cfg.linears[idx]
+    rng = np.random.default_rng([tensor_seed(cfg.index, idx, "W"), 4242])
+    s = cfg.dy_std * float(np.sqrt(cfg.M))
+    shape = (lin.N, lin.K)
+    g = (s * rng.standard_normal(shape, dtype=np.float32)).astype(np.float32)
+    m_prev = (s * np.sqrt((1 - beta1) / (1 + beta1)) * rng.standard_normal(shape, dtype=np.float32)).astype(np.float32)
+    v_prev = (s * s * np.maximum(1.0 + 0.05 * rng.standard_normal(shape, dtype=np.float32), 0.05)).astype(np.float32)
+    m = (beta1 * m_prev + (1 - beta1) * g).astype(np.float32)
+    v = (beta2 * v_prev + (1 - beta2) * g * g).astype(np.float32)
+    return m, v, g
+
+
 def make_layer(cfg: Config) -> LayerTensors:
     t = LayerTensors(cfg)
     for l in cfg.linears:

@@ -100,6 +100,37 @@ def test_loss_divergence_host_function_against_oracle():
     assert math.isnan(snip.snip_loss_divergence(-1.0, 1.0, 4, 1.0, 1.0, 4, 4))
 
 
+def test_weight_divergence_host_function_against_oracle():
+    import math
+    import numpy as np
+    import oracle
+    snip = lib()
+    rng = np.random.default_rng(61)
+    for _ in range(100):
+        alpha = float(10.0 ** rng.uniform(-6, -2))
+        b1, b2 = float(rng.uniform(0.5, 0.99)), float(rng.uniform(0.9, 0.9999))
+        t = int(rng.integers(1, 100000))
+        s, e = (float(x) for x in 10.0 ** rng.uniform(-10, 12, size=2))
+        n, k = (int(x) for x in rng.integers(1, 1 << 16, size=2))
+        want = oracle.weight_divergence(alpha, b1, b2, t, s, e, n, k)
+        assert math.isclose(snip.snip_weight_divergence(alpha, b1, b2, t, s, e, n, k), want, rel_tol=1e-13)
+    assert math.isnan(snip.snip_weight_divergence(1e-3, 0.9, 0.999, 0, 1.0, 1.0, 4, 4))
+    assert math.isnan(snip.snip_weight_divergence(1e-3, 1.0, 0.999, 1, 1.0, 1.0, 4, 4))
+
+
+def test_adamw_validation():
+    snip = lib()
+    L = snip._lib()
+    fake = ctypes.c_void_p(0x1000)
+    ws = snip.workspace_bytes(0, 0)
+    assert L.snip_adamw_sensitivity(None, fake, fake, 1, 8, 0.9, 0.999, 1e-8, fake, fake, ws, None) == 1
+    assert L.snip_adamw_sensitivity(fake, fake, fake, 1, -1, 0.9, 0.999, 1e-8, fake, fake, ws, None) == 2
+    assert L.snip_adamw_sensitivity(fake, fake, fake, 5, 8, 0.9, 0.999, 1e-8, fake, fake, ws, None) == 3
+    assert L.snip_adamw_sensitivity(fake, fake, fake, 1, 8, 1.5, 0.999, 1e-8, fake, fake, ws, None) == 3
+    assert L.snip_adamw_sensitivity(fake, fake, ctypes.c_void_p(0x1004), 1, 8, 0.9, 0.999, 1e-8, fake, fake, ws, None) == 4
+    assert L.snip_adamw_sensitivity(fake, fake, fake, 1, 8, 0.9, 0.999, 1e-8, fake, fake, 16, None) == 5
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     from paper_2602_01410_amd import snip
     monkeypatch.setattr(snip, "_handle", None)
