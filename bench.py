@@ -37,6 +37,8 @@ def parse():
     p.add_argument("--config", type=int, default=4, help="workload configuration 1..5 (default: Llama-7B-shaped layer)")
     p.add_argument("--plan", type=str, default=None, help="fp4 | fp8 | mixNN | tensor (default: the config's mixed plan)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-next-rows", action="store_true",
+                   help="skip the extra measurements of the stochastic-rounding and AdamW-sensitivity kernels")
     p.add_argument("--output-norms", action="store_true",
                    help="use the GEMM variants that also return the squared Frobenius norm of Y, dX, dW")
     p.add_argument("--microbench", action="store_true",
@@ -126,6 +128,39 @@ class Layer:
             e = torch.cuda.Event(enable_timing=True)
             e.record()
             ev.append((("end",), e))
+
+
+def next_rows(cfg, layer, snip, wl, reps=10):
+    """Throughput of the variants beyond the core path, on this configuration's largest linear: FP4
+    quantization with stochastic rounding of its output gradient (both axes) and the AdamW sensitivity
+    reduction over its weight's optimizer state.  Measured after the timed region; not part of `value`."""
+    lin = max(cfg.linears, key=lambda l: l.N * l.K)
+    dy = layer.src[("dY", lin.name)]
+
+    def rate(f, nbytes):
+        for _ in range(2):
+            f()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            f()
+        b.record()
+        torch.cuda.synchronize()
+        return nbytes / (a.elapsed_time(b) * 1e-3 / reps) / 1e9
+
+    out = {"linear": lin.name}
+    qbytes = dy.numel() * (2 + 0.5 + 1 / 32)
+    for axis, tag in ((snip.ROW, "row"), (snip.COL, "col")):
+        sr, sc = (dy.shape[0], dy.shape[1]) if axis == snip.ROW else (dy.shape[1], dy.shape[0])
+        q = snip.alloc_qtensor(sr, sc, snip.FP4)
+        out[f"sr_quantize_{tag}_gbps"] = rate(lambda: snip.snip_quantize_sr_fp4(dy, axis, seed=1, out=q), qbytes)
+        out[f"rne_quantize_{tag}_gbps"] = rate(lambda: snip.snip_quantize(dy, snip.FP4, axis, out=q), qbytes)
+        del q
+    m, v, g = (torch.from_numpy(t).cuda().reshape(-1) for t in wl.make_optimizer_state(cfg, lin.name))
+    o = torch.empty(1, dtype=torch.float64, device="cuda")
+    out["adamw_sensitivity_gbps"] = rate(lambda: snip.snip_adamw_sensitivity(m, v, g, 0.9, 0.999, 1e-8, out=o, workspace=layer.ws),
+                                         m.numel() * 12)
+    return out
 
 
 def cpu_baseline(cfg, wl):
@@ -227,6 +262,8 @@ def main():
                      "traffic": MEASURED_TRAFFIC.get((cfg.index, plan_name, KERNEL_NAME[dom])),
                      "launches": dn, "avg_launch_us": dsec / dn * 1e6, "avg_flop_per_launch": dfl / dn},
     }
+    if not args.no_next_rows:
+        out["next_rows"] = next_rows(cfg, layer, snip, wl)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, wl)
     print(json.dumps(out))

@@ -613,19 +613,37 @@ size_t workspace_bytes(int64_t rows, int64_t cols)
     return kPartialBytes + (size_t)kMaxColSplits * (size_t)cols * 3 * sizeof(float);
 }
 
+// Workgroups for `units` equal work units that waves take in turn: as many waves as give every wave the
+// same number of units (the last one possibly fewer), at most kStreamWaves.  11008 units on 8192 waves would
+// leave three quarters of the device idle during the second turn; 5504 waves take two units each.
+static int balanced_blocks(int64_t units)
+{
+    if (units <= 0) return 1;
+    const int64_t per_wave = (units + kStreamWaves - 1) / kStreamWaves;
+    const int64_t waves = (units + per_wave - 1) / per_wave;
+    return (int)((waves + kWavesPerBlock - 1) / kWavesPerBlock);
+}
+
+// Returns the number of workgroups launched (= partial-sum slots used, times kWavesPerBlock).
 template <int FMT, int RULE, bool STATS, bool SR = false>
-static void launch_q(const QuantArgs& a, float* partials, hipStream_t s)
+static int launch_q(const QuantArgs& a, float* partials, hipStream_t s)
 {
     const uint2 seed = make_uint2((unsigned)a.sr_seed, (unsigned)(a.sr_seed >> 32));
+    int blocks;
     // pitch of the block-major scale copy = padded number of STORED rows
-    if (a.axis == 0)
-        hipLaunchKernelGGL((quant_row_kernel<FMT, RULE, STATS, SR>), dim3(kStreamBlocks), dim3(256), 0, s,
+    if (a.axis == 0) {
+        blocks = balanced_blocks(((a.rows + kUnroll - 1) / kUnroll) * ((a.cols + kSeg - 1) / kSeg));
+        hipLaunchKernelGGL((quant_row_kernel<FMT, RULE, STATS, SR>), dim3(blocks), dim3(256), 0, s,
                            a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, a.scales_g4,
                            g4_pitch(a.rows), partials, seed);
-    else
-        hipLaunchKernelGGL((quant_col_kernel<FMT, RULE, STATS, SR>), dim3(kStreamBlocks), dim3(256), 0, s,
+    } else {
+        const int64_t nrb = a.rows / kBlock;
+        blocks = balanced_blocks(((a.cols + kColsPerWave - 1) / kColsPerWave) * ((nrb + kRowBlocksPerUnit - 1) / kRowBlocksPerUnit));
+        hipLaunchKernelGGL((quant_col_kernel<FMT, RULE, STATS, SR>), dim3(blocks), dim3(256), 0, s,
                            a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, a.scales_g4,
                            g4_pitch(a.cols), partials, seed);
+    }
+    return blocks;
 }
 
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
@@ -646,22 +664,23 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
         return hipGetLastError();
     }
     const int key = (a.fmt << 2) | (a.rule << 1) | (st ? 1 : 0);
+    int blocks = 0;
     switch (key) {
-        case 0: launch_q<kFP8, 0, false>(a, partials, s); break;
-        case 1: launch_q<kFP8, 0, true>(a, partials, s); break;
-        case 2: launch_q<kFP8, 1, false>(a, partials, s); break;
-        case 3: launch_q<kFP8, 1, true>(a, partials, s); break;
-        case 4: launch_q<kFP4, 0, false>(a, partials, s); break;
-        case 5: launch_q<kFP4, 0, true>(a, partials, s); break;
-        case 6: launch_q<kFP4, 1, false>(a, partials, s); break;
-        case 7: launch_q<kFP4, 1, true>(a, partials, s); break;
+        case 0: blocks = launch_q<kFP8, 0, false>(a, partials, s); break;
+        case 1: blocks = launch_q<kFP8, 0, true>(a, partials, s); break;
+        case 2: blocks = launch_q<kFP8, 1, false>(a, partials, s); break;
+        case 3: blocks = launch_q<kFP8, 1, true>(a, partials, s); break;
+        case 4: blocks = launch_q<kFP4, 0, false>(a, partials, s); break;
+        case 5: blocks = launch_q<kFP4, 0, true>(a, partials, s); break;
+        case 6: blocks = launch_q<kFP4, 1, false>(a, partials, s); break;
+        case 7: blocks = launch_q<kFP4, 1, true>(a, partials, s); break;
         default: return hipErrorInvalidValue;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (st) {
         hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(kReduceThreads), 0, s,
-                           (const float*)partials, kStreamWaves, a.fmt == kFP4 ? 1 : 2, a.stats);
+                           (const float*)partials, blocks * kWavesPerBlock, a.fmt == kFP4 ? 1 : 2, a.stats);
         e = hipGetLastError();
     }
     return e;
@@ -676,13 +695,14 @@ hipError_t launch_stats(const StatsArgs& a, hipStream_t s)
     }
     int npart;
     if (a.axis == 0) {
+        const int blocks = balanced_blocks(a.rows);             // a wave per row
         if (a.rule == 0)
-            hipLaunchKernelGGL((stats_row_kernel<0>), dim3(kStreamBlocks), dim3(256), 0, s,
+            hipLaunchKernelGGL((stats_row_kernel<0>), dim3(blocks), dim3(256), 0, s,
                                a.x, (int)a.rows, (int)a.cols, a.ld, partials, a.per_line);
         else
-            hipLaunchKernelGGL((stats_row_kernel<1>), dim3(kStreamBlocks), dim3(256), 0, s,
+            hipLaunchKernelGGL((stats_row_kernel<1>), dim3(blocks), dim3(256), 0, s,
                                a.x, (int)a.rows, (int)a.cols, a.ld, partials, a.per_line);
-        npart = kStreamWaves;
+        npart = blocks * kWavesPerBlock;
     } else {
         int gx;
         const int nsplit = col_splits(a.rows, a.cols, &gx);
