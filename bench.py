@@ -37,6 +37,7 @@ def parse():
     p.add_argument("--config", type=int, default=4, help="workload configuration 1..5 (default: Llama-7B-shaped layer)")
     p.add_argument("--plan", type=str, default=None, help="fp4 | fp8 | mixNN | tensor (default: the config's mixed plan)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     p.add_argument("--no-next-rows", action="store_true",
                    help="skip the extra measurements of the stochastic-rounding and AdamW-sensitivity kernels")
     p.add_argument("--output-norms", action="store_true",
@@ -128,6 +129,29 @@ class Layer:
             e = torch.cuda.Event(enable_timing=True)
             e.record()
             ev.append((("end",), e))
+
+
+def graph_replay(layer, steps, warmup):
+    """The same step captured once into a HIP graph and replayed: what the launch gaps of the ~150 kernel
+    launches of a step cost.  Reported beside `value` (which times ordinary launches with per-call events)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        layer.step()                                   # everything the step touches exists before capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        layer.step()
+    for _ in range(max(1, warmup)):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    return {"ms_per_step": ms, "value": layer.flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s"}
 
 
 def next_rows(cfg, layer, snip, wl, reps=10):
@@ -262,6 +286,8 @@ def main():
                      "traffic": MEASURED_TRAFFIC.get((cfg.index, plan_name, KERNEL_NAME[dom])),
                      "launches": dn, "avg_launch_us": dsec / dn * 1e6, "avg_flop_per_launch": dfl / dn},
     }
+    if not args.no_graph:
+        out["hip_graph"] = graph_replay(layer, args.steps, args.warmup)
     if not args.no_next_rows:
         out["next_rows"] = next_rows(cfg, layer, snip, wl)
     if not args.no_cpu_baseline:
