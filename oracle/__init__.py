@@ -81,6 +81,12 @@ def _load():
         lib.oracle_adamw_sensitivity_sq.argtypes = [vp, vp, vp, i64, dbl, dbl, dbl]
         lib.oracle_weight_divergence.restype = dbl
         lib.oracle_weight_divergence.argtypes = [dbl, dbl, dbl, i64, dbl, dbl, i64, i64]
+        lib.oracle_quantize_paper.restype = ci
+        lib.oracle_quantize_paper.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp]
+        lib.oracle_dequantize_paper.restype = ci
+        lib.oracle_dequantize_paper.argtypes = [vp, vp, i64, i64, ci, ci, vp]
+        lib.oracle_stats_paper.restype = ci
+        lib.oracle_stats_paper.argtypes = [vp, i64, i64, i64, ci, ci, vp]
         lib.oracle_round_output.restype = dbl
         lib.oracle_round_output.argtypes = [dbl, ci]
         lib.oracle_output_sum_sq.restype = dbl
@@ -292,3 +298,38 @@ def weight_divergence(alpha: float, beta1: float, beta2: float, t: int, sens_sq:
                       N: int, K: int) -> float:
     return float(_load().oracle_weight_divergence(float(alpha), float(beta1), float(beta2), int(t),
                                                   float(sens_sq), float(err_g_sq), N, K))
+
+
+TILE_1x128, BLOCK_128x128 = 1, 128      # group_rows of the paper's two granularities
+
+
+def quantize_paper(x_bf16_bits, fmt: int, axis: int = ROW, group_rows: int = TILE_1x128):
+    """The paper's recipe (real-valued scale FPX_MAX / amax per 1x128 tile or 128x128 block):
+    (codes, scales float32 [ceil(SR/group_rows), SC/128]) in the stored orientation."""
+    x = _bf16_2d(x_bf16_bits)
+    rows, cols = x.shape
+    sr, sc = stored_shape(rows, cols, axis)
+    codes = np.zeros((sr, sc if fmt == FP8 else sc // 2), dtype=np.uint8)
+    scales = np.zeros(((sr + group_rows - 1) // group_rows, sc // 128), dtype=np.float32)
+    _check(_load().oracle_quantize_paper(_ptr(x), rows, cols, cols, fmt, axis, group_rows, _ptr(codes), _ptr(scales)),
+           "quantize_paper")
+    return codes, scales
+
+
+def dequantize_paper(codes, scales, fmt: int, group_rows: int = TILE_1x128) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    sr = codes.shape[0]
+    sc = codes.shape[1] if fmt == FP8 else codes.shape[1] * 2
+    out = np.empty((sr, sc), dtype=np.float64)
+    _check(_load().oracle_dequantize_paper(_ptr(codes), _ptr(scales), sr, sc, fmt, group_rows, _ptr(out)), "dequantize_paper")
+    return out
+
+
+def stats_paper(x_bf16_bits, axis: int = ROW, group_rows: int = TILE_1x128) -> np.ndarray:
+    """(sum x^2, sum (q4(x)-x)^2, sum (q8(x)-x)^2) under the paper's recipe."""
+    x = _bf16_2d(x_bf16_bits)
+    rows, cols = x.shape
+    out = np.zeros(3, dtype=np.float64)
+    _check(_load().oracle_stats_paper(_ptr(x), rows, cols, cols, axis, group_rows, _ptr(out)), "stats_paper")
+    return out

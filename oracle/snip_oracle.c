@@ -518,3 +518,121 @@ double oracle_weight_divergence(double alpha, double beta1, double beta2, int64_
     double corr = sqrt(1.0 - pow(beta2, (double)t)) / (1.0 - pow(beta1, (double)t));
     return alpha * corr * sqrt(sens_sq) * sqrt(err_g_sq) / sqrt((double)N * (double)K);
 }
+
+/* ---- the paper's own quantization recipe (Sec. 2.3 and Sec. 5.1) ---------------------- */
+
+/* Sec. 2.3: scale = FPX_MAX / max|x| over a scaling group, y = Quant(x * scale), and the
+ * value the GEMM sees is y / scale.  Sec. 5.1: the groups are 1x128 tiles for activations and
+ * gradients and 128x128 blocks for weights.  Unlike the power-of-two block scales above, this
+ * scale is a real number and x * scale is not exact, so the precision of those two steps is
+ * part of the definition; it is fp32 here (one correctly rounded division, one correctly
+ * rounded product), the working precision of the GPU path:
+ *     s = (float)FPX_MAX / amax          (amax = 0: s = 1;  s is capped at 2^126 so that a
+ *                                         group of denormal-sized values does not overflow it)
+ *     t = (float)x * s
+ *     code = nearest FPX value to t, ties to even, saturating
+ * The scale array holds s as fp32, one per group, in the stored orientation:
+ *     group_rows = 1   (tiles):  [SR][SC/128]
+ *     group_rows = 128 (blocks): [ceil(SR/128)][SC/128]
+ * SC must be a multiple of 128.  A group that contains an infinity or a NaN gets scale NaN and
+ * zero codes.  Codes are laid out as in oracle_quantize. */
+static float paper_group_scale(const uint16_t* src, int64_t ld, int axis, int fmt,
+                               int64_t r0, int64_t r1, int64_t c0, int64_t c1)
+{
+    float amax = 0.0f;
+    int bad = 0;
+    for (int64_t r = r0; r < r1; ++r)
+        for (int64_t c = c0; c < c1; ++c) {
+            float x = (float)oracle_bf16_to_f64(stored_elem(src, ld, axis, r, c));
+            if (isnan(x) || isinf(x)) bad = 1;
+            else if (fabsf(x) > amax) amax = fabsf(x);
+        }
+    if (bad) return NAN;
+    if (amax == 0.0f) return 1.0f;
+    float s = (float)oracle_fmt_max(fmt) / amax;
+    if (!(s <= 0x1p126f)) s = 0x1p126f;
+    return s;
+}
+
+int oracle_quantize_paper(const uint16_t* src, int64_t rows, int64_t cols, int64_t ld,
+                          int fmt, int axis, int group_rows, uint8_t* codes, float* scales)
+{
+    if (!src || !codes || !scales) return -1;
+    if ((fmt != 0 && fmt != 1) || (axis != 0 && axis != 1) || (group_rows != 1 && group_rows != 128)) return -1;
+    if (rows < 0 || cols < 0 || ld < cols) return -1;
+    const int64_t SR = axis == 0 ? rows : cols;
+    const int64_t SC = axis == 0 ? cols : rows;
+    if (SC % 128) return -1;
+    const int64_t ng = SC / 128;
+    if (fmt == 1) memset(codes, 0, (size_t)(SR * SC / 2));
+    for (int64_t r0 = 0; r0 < SR; r0 += group_rows) {
+        int64_t r1 = r0 + group_rows < SR ? r0 + group_rows : SR;
+        for (int64_t gcol = 0; gcol < ng; ++gcol) {
+            float s = paper_group_scale(src, ld, axis, fmt, r0, r1, gcol * 128, gcol * 128 + 128);
+            scales[(r0 / group_rows) * ng + gcol] = s;
+            for (int64_t r = r0; r < r1; ++r)
+                for (int64_t c = gcol * 128; c < gcol * 128 + 128; ++c) {
+                    unsigned code = 0u;
+                    if (!isnan(s)) {
+                        float x = (float)oracle_bf16_to_f64(stored_elem(src, ld, axis, r, c));
+                        float t = x * s;
+                        code = oracle_encode_rne(fmt, (double)t);
+                    }
+                    int64_t e = r * SC + c;
+                    if (fmt == 0) codes[e] = (uint8_t)code;
+                    else codes[e >> 1] |= (uint8_t)(code << (4 * (e & 1)));
+                }
+        }
+    }
+    return 0;
+}
+
+/* Value the GEMM sees for every element: decode(code) / s, in double, stored orientation. */
+int oracle_dequantize_paper(const uint8_t* codes, const float* scales, int64_t SR, int64_t SC,
+                            int fmt, int group_rows, double* out)
+{
+    if (!codes || !scales || !out || SC % 128 || (fmt != 0 && fmt != 1)) return -1;
+    const int64_t ng = SC / 128;
+    for (int64_t r = 0; r < SR; ++r)
+        for (int64_t c = 0; c < SC; ++c) {
+            int64_t e = r * SC + c;
+            unsigned code = fmt == 0 ? codes[e] : (codes[e >> 1] >> (4 * (e & 1))) & 0xFu;
+            double s = (double)scales[(r / group_rows) * ng + c / 128];
+            out[e] = isnan(s) ? NAN : oracle_decode(fmt, code) / s;
+        }
+    return 0;
+}
+
+/* Step-1 statistics under the paper's recipe: out3 = { sum x^2, sum (q4(x)-x)^2, sum (q8(x)-x)^2 }
+ * with q = dequantize(quantize(x)) as above, sums in index order in double. */
+int oracle_stats_paper(const uint16_t* src, int64_t rows, int64_t cols, int64_t ld,
+                       int axis, int group_rows, double* out3)
+{
+    if (!src || !out3) return -1;
+    const int64_t SR = axis == 0 ? rows : cols;
+    const int64_t SC = axis == 0 ? cols : rows;
+    if (rows < 0 || cols < 0 || ld < cols || SC % 128) return -1;
+    size_t n = (size_t)SR * (size_t)SC;
+    size_t ngroups = (size_t)((SR + group_rows - 1) / group_rows) * (size_t)(SC / 128);
+    uint8_t* codes = (uint8_t*)malloc(n ? n : 1);
+    float* scales = (float*)malloc((ngroups ? ngroups : 1) * sizeof(float));
+    double* q = (double*)malloc((n ? n : 1) * sizeof(double));
+    int rc = (codes && scales && q) ? 0 : -1;
+    out3[0] = out3[1] = out3[2] = 0.0;
+    for (int fmt = 1; fmt >= 0 && rc == 0; --fmt) {
+        rc = oracle_quantize_paper(src, rows, cols, ld, fmt, axis, group_rows, codes, scales);
+        if (rc == 0) rc = oracle_dequantize_paper(codes, scales, SR, SC, fmt, group_rows, q);
+        if (rc != 0) break;
+        double s0 = 0.0, se = 0.0;
+        for (int64_t r = 0; r < SR; ++r)
+            for (int64_t c = 0; c < SC; ++c) {
+                double x = oracle_bf16_to_f64(stored_elem(src, ld, axis, r, c));
+                double d = q[r * SC + c] - x;
+                s0 += x * x; se += d * d;
+            }
+        out3[0] = s0;
+        out3[fmt == 1 ? 1 : 2] = se;
+    }
+    free(codes); free(scales); free(q);
+    return rc;
+}
