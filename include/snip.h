@@ -69,6 +69,12 @@ typedef enum {
 
 typedef enum { SNIP_OUT_BF16 = 0, SNIP_OUT_FP32 = 1 } snip_out_dtype;
 
+/* Scaling groups of the paper's own recipe, in the stored orientation. */
+typedef enum {
+    SNIP_GROUP_TILE_1x128 = 1,      /* 128 consecutive elements of a stored row (activations, gradients) */
+    SNIP_GROUP_BLOCK_128x128 = 128  /* 128 stored rows x 128 elements (weights) */
+} snip_group;
+
 /* A quantized matrix in its stored orientation: `cols` is the blocked (contraction) extent.
  *   codes : device. FP8: rows*cols bytes, row-major. FP4: rows*cols/2 bytes, row-major, element
  *           2i in the low nibble and 2i+1 in the high nibble of byte i. 16-byte aligned.
@@ -204,6 +210,34 @@ snip_status snip_gemm_wgrad_norm(const snip_layer_plan* plan, const snip_qtensor
  * Returns NaN for a non-positive extent or a negative or NaN argument. */
 double snip_loss_divergence(double grad_x_sq, double err_x_sq, int64_t m,
                             double grad_w_sq, double err_w_sq, int64_t n, int64_t k);
+
+/* ---- the paper's own quantization recipe (Sec. 2.3, Sec. 5.1) -------------------------- */
+/* Sec. 2.3 scales a group by the real number s = FPX_MAX / max|x|, casts x * s to FPX and divides
+ * by s afterwards; Sec. 5.1 uses 1x128 tiles for activations and gradients and 128x128 blocks
+ * for weights.  These calls implement exactly that, next to the power-of-two 32-element blocks
+ * of snip_quantize, so that the error statistics of the paper's configuration can be produced.
+ * s and x * s are formed in fp32 (one correctly rounded division, one correctly rounded
+ * product), then rounded to nearest even onto the FPX grid, saturating; s = 1 for an all-zero
+ * group, s is capped at 2^126, and a group with an infinity or NaN gets s = NaN and zero codes.
+ *   x, rows, cols, ld, axis: as for snip_quantize, but the blocked extent (cols for AXIS_ROW,
+ *           rows for AXIS_COL) must be a multiple of 128.
+ *   codes : device, layout as snip_qtensor.codes (stored orientation), 16-byte aligned.
+ *   scales: device, fp32, [stored rows][stored cols / 128] for tiles,
+ *           [ceil(stored rows / 128)][stored cols / 128] for blocks; snip_paper_scale_bytes.
+ * The codes are not consumed by the GEMMs of this library (the matrix instruction applies
+ * power-of-two scales to 32-element blocks only). */
+size_t snip_paper_scale_bytes(int64_t stored_rows, int64_t stored_cols, snip_group group);
+snip_status snip_quantize_paper(const void* x, int64_t rows, int64_t cols, int64_t ld,
+                                snip_fmt fmt, snip_axis axis, snip_group group,
+                                void* codes, float* scales, void* stream);
+
+/* Squared Frobenius norms of x and of q(x) - x for both formats under that recipe (q(x) = code / s).
+ *   out: device, one snip_stats.  workspace: device, required,
+ *   >= snip_paper_workspace_bytes(rows, cols), 16-byte aligned. */
+size_t snip_paper_workspace_bytes(int64_t rows, int64_t cols);
+snip_status snip_quant_error_stats_paper(const void* x, int64_t rows, int64_t cols, int64_t ld,
+                                         snip_axis axis, snip_group group, snip_stats* out,
+                                         void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- AdamW factor of the weight-divergence estimate (Sec. 4.3.2) ---------------------- */
 /* With m = beta1 m' + (1-beta1) g and v = beta2 v' + (1-beta2) g^2 (the AdamW moments after the

@@ -213,6 +213,60 @@ double snip_loss_divergence(double grad_x_sq, double err_x_sq, int64_t m, double
     return std::hypot(tx, tw);
 }
 
+static snip_status check_paper(const void* x, int64_t rows, int64_t cols, int64_t ld, int axis, int group)
+{
+    snip_status st = check_source(x, rows, cols, ld, axis, SNIP_SCALE_NO_OVERFLOW);
+    if (st != SNIP_OK) return st;
+    if (group != SNIP_GROUP_TILE_1x128 && group != SNIP_GROUP_BLOCK_128x128) return SNIP_ERR_FORMAT;
+    if ((axis == SNIP_AXIS_ROW ? cols : rows) % 128 != 0) return SNIP_ERR_SHAPE;
+    return SNIP_OK;
+}
+
+size_t snip_paper_scale_bytes(int64_t stored_rows, int64_t stored_cols, snip_group group)
+{
+    if (stored_rows < 0 || stored_cols < 0 || stored_cols % 128 != 0) return 0;
+    if (group != SNIP_GROUP_TILE_1x128 && group != SNIP_GROUP_BLOCK_128x128) return 0;
+    const int64_t gr = group == SNIP_GROUP_TILE_1x128 ? stored_rows : (stored_rows + 127) / 128;
+    return (size_t)gr * (size_t)(stored_cols / 128) * sizeof(float);
+}
+
+size_t snip_paper_workspace_bytes(int64_t rows, int64_t cols)
+{
+    if (rows < 0 || cols < 0) return 0;
+    return paper_workspace_bytes(rows, cols);
+}
+
+snip_status snip_quantize_paper(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_fmt fmt, snip_axis axis,
+                                snip_group group, void* codes, float* scales, void* stream)
+{
+    if (!valid_fmt(fmt)) return SNIP_ERR_FORMAT;
+    snip_status st = check_paper(x, rows, cols, ld, axis, group);
+    if (st != SNIP_OK) return st;
+    if ((!codes || !scales) && rows > 0 && cols > 0) return SNIP_ERR_NULL;
+    if (!aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return SNIP_ERR_LAYOUT;
+    PaperArgs a;
+    a.x = (const uint16_t*)x; a.rows = rows; a.cols = cols; a.ld = ld; a.fmt = fmt; a.axis = axis;
+    a.blocks = group == SNIP_GROUP_BLOCK_128x128;
+    a.codes = (uint8_t*)codes; a.scales = scales; a.stats = nullptr; a.workspace = nullptr;
+    return launch_paper(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
+}
+
+snip_status snip_quant_error_stats_paper(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_axis axis,
+                                         snip_group group, snip_stats* out, void* workspace, size_t workspace_bytes_,
+                                         void* stream)
+{
+    snip_status st = check_paper(x, rows, cols, ld, axis, group);
+    if (st != SNIP_OK) return st;
+    if (!out) return SNIP_ERR_NULL;
+    if (!workspace || workspace_bytes_ < paper_workspace_bytes(rows, cols)) return SNIP_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SNIP_ERR_LAYOUT;
+    PaperArgs a;
+    a.x = (const uint16_t*)x; a.rows = rows; a.cols = cols; a.ld = ld; a.fmt = SNIP_FP8_E4M3; a.axis = axis;
+    a.blocks = group == SNIP_GROUP_BLOCK_128x128;
+    a.codes = nullptr; a.scales = nullptr; a.stats = (double*)out; a.workspace = workspace;
+    return launch_paper(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
+}
+
 snip_status snip_adamw_sensitivity(const float* m, const float* v, const void* g, snip_out_dtype g_dtype,
                                    int64_t n, float beta1, float beta2, float eps, double* sum_sq,
                                    void* workspace, size_t workspace_bytes_, void* stream)

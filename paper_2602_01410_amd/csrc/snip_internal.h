@@ -64,6 +64,21 @@ struct AdamwArgs {
     void* workspace;      // room for kStreamWaves floats
 };
 
+// The paper's own recipe (real-valued scale per 1x128 tile or 128x128 block): quantize (stats == nullptr)
+// or statistics of both formats (stats != nullptr; codes / scales unused).
+struct PaperArgs {
+    const uint16_t* x;
+    int64_t rows, cols, ld;
+    int fmt, axis;
+    bool blocks;           // false: 1x128 tiles, true: 128x128 blocks (stored orientation)
+    uint8_t* codes;
+    float* scales;
+    double* stats;         // device, 3 doubles
+    void* workspace;       // statistics only: paper_workspace_bytes(rows, cols)
+};
+size_t paper_workspace_bytes(int64_t rows, int64_t cols);
+hipError_t launch_paper(const PaperArgs& a, hipStream_t s);
+
 size_t workspace_bytes(int64_t rows, int64_t cols);
 hipError_t launch_adamw_sensitivity(const AdamwArgs& a, hipStream_t s);
 // out[0] = sum of partials[0..n) in index order, in double (one workgroup); n may be 0

@@ -26,7 +26,9 @@ EXPORTS = ("snip_qtensor_code_bytes", "snip_qtensor_scale_bytes", "snip_qtensor_
            "snip_quantize", "snip_gemm_fwd", "snip_gemm_dgrad", "snip_gemm_wgrad",
            "snip_quant_error_stats", "snip_status_string",
            "snip_gemm_workspace_bytes", "snip_gemm_fwd_norm", "snip_gemm_dgrad_norm", "snip_gemm_wgrad_norm",
-           "snip_loss_divergence", "snip_quantize_sr_fp4", "snip_adamw_sensitivity", "snip_weight_divergence")
+           "snip_loss_divergence", "snip_quantize_sr_fp4", "snip_adamw_sensitivity", "snip_weight_divergence",
+           "snip_paper_scale_bytes", "snip_paper_workspace_bytes", "snip_quantize_paper",
+           "snip_quant_error_stats_paper")
 
 
 class SnipError(RuntimeError):
@@ -75,6 +77,14 @@ def _lib():
                            vp, i64, ci, vp, sz, vp]
         lib.snip_quantize_sr_fp4.restype = ci
         lib.snip_quantize_sr_fp4.argtypes = [vp, i64, i64, i64, ci, ci, ctypes.c_uint64, ctypes.POINTER(_QTensorC), vp]
+        lib.snip_paper_scale_bytes.restype = sz
+        lib.snip_paper_scale_bytes.argtypes = [i64, i64, ci]
+        lib.snip_paper_workspace_bytes.restype = sz
+        lib.snip_paper_workspace_bytes.argtypes = [i64, i64]
+        lib.snip_quantize_paper.restype = ci
+        lib.snip_quantize_paper.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp, vp]
+        lib.snip_quant_error_stats_paper.restype = ci
+        lib.snip_quant_error_stats_paper.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, sz, vp]
         cf, cd = ctypes.c_float, ctypes.c_double
         lib.snip_adamw_sensitivity.restype = ci
         lib.snip_adamw_sensitivity.argtypes = [vp, vp, vp, ci, i64, cf, cf, cf, vp, vp, sz, vp]
@@ -199,6 +209,35 @@ def snip_quantize_sr_fp4(x: torch.Tensor, axis: int = ROW, rule: int = NO_OVERFL
     q = out.c_struct()
     _check(_lib().snip_quantize_sr_fp4(ptr, rows, cols, ld, axis, rule, int(seed) & (2 ** 64 - 1), ctypes.byref(q),
                                        _stream(stream)), "snip_quantize_sr_fp4")
+    return out
+
+
+TILE_1x128, BLOCK_128x128 = 1, 128
+
+
+def snip_quantize_paper(x: torch.Tensor, fmt: int, axis: int = ROW, group: int = TILE_1x128, stream=None):
+    """The paper's recipe: returns (codes uint8 [SR, SC or SC/2], scales float32 [SR or ceil(SR/128), SC/128])."""
+    ptr, rows, cols, ld = _src(x)
+    sr, sc = (rows, cols) if axis == ROW else (cols, rows)
+    codes = torch.empty((sr, sc if fmt == FP8 else sc // 2), dtype=torch.uint8, device=x.device)
+    nbytes = int(_lib().snip_paper_scale_bytes(sr, sc, group))
+    scales = torch.empty((nbytes // 4 // max(1, sc // 128), sc // 128) if sc >= 128 else (0, 0), dtype=torch.float32,
+                         device=x.device)
+    _check(_lib().snip_quantize_paper(ptr, rows, cols, ld, fmt, axis, group, codes.data_ptr() if codes.numel() else None,
+                                      scales.data_ptr() if scales.numel() else None, _stream(stream)), "snip_quantize_paper")
+    return codes, scales
+
+
+def snip_quant_error_stats_paper(x: torch.Tensor, axis: int = ROW, group: int = TILE_1x128,
+                                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                                 stream=None) -> torch.Tensor:
+    ptr, rows, cols, ld = _src(x)
+    if out is None:
+        out = alloc_stats(x.device)
+    if workspace is None:
+        workspace = torch.empty(int(_lib().snip_paper_workspace_bytes(rows, cols)), dtype=torch.uint8, device=x.device)
+    _check(_lib().snip_quant_error_stats_paper(ptr, rows, cols, ld, axis, group, out.data_ptr(), workspace.data_ptr(),
+                                               workspace.numel(), _stream(stream)), "snip_quant_error_stats_paper")
     return out
 
 
