@@ -224,12 +224,32 @@ double snip_loss_divergence(double grad_x_sq, double err_x_sq, int64_t m,
  *   codes : device, layout as snip_qtensor.codes (stored orientation), 16-byte aligned.
  *   scales: device, fp32, [stored rows][stored cols / 128] for tiles,
  *           [ceil(stored rows / 128)][stored cols / 128] for blocks; snip_paper_scale_bytes.
- * The codes are not consumed by the GEMMs of this library (the matrix instruction applies
- * power-of-two scales to 32-element blocks only). */
+ * The codes are consumed by snip_gemm_paper below, not by snip_gemm_fwd/dgrad/wgrad (the matrix
+ * instruction applies power-of-two scales to 32-element blocks only). */
 size_t snip_paper_scale_bytes(int64_t stored_rows, int64_t stored_cols, snip_group group);
 snip_status snip_quantize_paper(const void* x, int64_t rows, int64_t cols, int64_t ld,
                                 snip_fmt fmt, snip_axis axis, snip_group group,
                                 void* codes, float* scales, void* stream);
+
+/* A matrix quantized by snip_quantize_paper, in its stored orientation (cols = contraction extent,
+ * a multiple of 128); scales as that call lays them out for `group`. */
+typedef struct {
+    const void*  codes;
+    const float* scales;
+    int64_t      rows, cols;
+    int32_t      fmt;      /* snip_fmt */
+    int32_t      group;    /* snip_group */
+} snip_ptensor;
+
+/* C[i][j] = sum_r (A[i][r] / sa) * (B[j][r] / sb) for operands of that recipe: the real-valued
+ * scales are applied in software once per 128-element slab of the contraction (the codes of a
+ * slab are multiplied on the matrix cores with unit scales into a fresh fp32 accumulator, which
+ * is folded into the result with the factor (1/sa)(1/sb)); fp32 accumulation, one rounding to
+ * the output type.  The three GEMMs of a linear layer are this call with the operand pairs
+ * listed for snip_gemm_fwd / dgrad / wgrad.  A NaN scale makes the rows or columns it covers NaN.
+ * Output layout and alignment as for the other GEMMs. */
+snip_status snip_gemm_paper(const snip_ptensor* a, const snip_ptensor* b, void* c, int64_t ld_out,
+                            snip_out_dtype out_dtype, void* stream);
 
 /* Squared Frobenius norms of x and of q(x) - x for both formats under that recipe (q(x) = code / s).
  *   out: device, one snip_stats.  workspace: device, required,

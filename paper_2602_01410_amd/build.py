@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libsnip_hip.so")
 MICROBENCH = os.path.join(_HERE, "snip_microbench")
-SOURCES = ("api.hip", "quant_kernels.hip", "gemm.hip", "gemm_fast.hip", "optim_kernels.hip", "paper_kernels.hip")
+SOURCES = ("api.hip", "quant_kernels.hip", "gemm.hip", "gemm_fast.hip", "optim_kernels.hip", "paper_kernels.hip", "gemm_paper.hip")
 
 
 def build_library(verbose: bool = False) -> str:

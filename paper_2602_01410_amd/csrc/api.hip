@@ -267,6 +267,39 @@ snip_status snip_quant_error_stats_paper(const void* x, int64_t rows, int64_t co
     return launch_paper(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
 }
 
+static snip_status check_ptensor(const snip_ptensor* q)
+{
+    if (!q) return SNIP_ERR_NULL;
+    if ((!q->codes || !q->scales) && q->rows > 0) return SNIP_ERR_NULL;
+    if (!valid_fmt(q->fmt)) return SNIP_ERR_FORMAT;
+    if (q->group != SNIP_GROUP_TILE_1x128 && q->group != SNIP_GROUP_BLOCK_128x128) return SNIP_ERR_FORMAT;
+    if (q->rows < 0 || q->cols <= 0 || q->cols % 128 != 0) return SNIP_ERR_SHAPE;
+    if (q->rows >= (int64_t)1 << 31 || q->cols >= (int64_t)1 << 31) return SNIP_ERR_SHAPE;
+    if (!aligned16(q->codes) || (reinterpret_cast<uintptr_t>(q->scales) & 3u)) return SNIP_ERR_LAYOUT;
+    return SNIP_OK;
+}
+
+snip_status snip_gemm_paper(const snip_ptensor* a, const snip_ptensor* b, void* c, int64_t ld_out,
+                            snip_out_dtype out_dtype, void* stream)
+{
+    snip_status st = check_ptensor(a);
+    if (st != SNIP_OK) return st;
+    st = check_ptensor(b);
+    if (st != SNIP_OK) return st;
+    if (!c && a->rows > 0 && b->rows > 0) return SNIP_ERR_NULL;
+    if (out_dtype != SNIP_OUT_BF16 && out_dtype != SNIP_OUT_FP32) return SNIP_ERR_FORMAT;
+    if (a->cols != b->cols) return SNIP_ERR_LAYOUT;
+    if (ld_out < b->rows) return SNIP_ERR_SHAPE;
+    if ((a->rows + 127) / 128 * ((b->rows + 127) / 128) >= (int64_t)1 << 31) return SNIP_ERR_SHAPE;
+    if (!aligned16(c) || ld_out % (out_dtype == SNIP_OUT_BF16 ? 8 : 4) != 0) return SNIP_ERR_LAYOUT;
+    GemmPaperArgs g;
+    g.a_codes = (const uint8_t*)a->codes; g.a_scales = a->scales; g.a_group = a->group; g.fmt_a = a->fmt;
+    g.b_codes = (const uint8_t*)b->codes; g.b_scales = b->scales; g.b_group = b->group; g.fmt_b = b->fmt;
+    g.I = a->rows; g.J = b->rows; g.R = a->cols;
+    g.c = c; g.ldc = ld_out; g.out_fp32 = out_dtype == SNIP_OUT_FP32;
+    return launch_gemm_paper(g, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
+}
+
 snip_status snip_adamw_sensitivity(const float* m, const float* v, const void* g, snip_out_dtype g_dtype,
                                    int64_t n, float beta1, float beta2, float eps, double* sum_sq,
                                    void* workspace, size_t workspace_bytes_, void* stream)

@@ -76,6 +76,13 @@ struct PaperArgs {
     double* stats;         // device, 3 doubles
     void* workspace;       // statistics only: paper_workspace_bytes(rows, cols)
 };
+struct GemmPaperArgs {
+    const uint8_t* a_codes; const float* a_scales; int a_group; int fmt_a;     // group: 1 (tiles) or 128 (blocks)
+    const uint8_t* b_codes; const float* b_scales; int b_group; int fmt_b;
+    int64_t I, J, R;      // C[I][J] = sum_r (A[I][r] / sa) (B[J][r] / sb)
+    void* c; int64_t ldc; int out_fp32;
+};
+hipError_t launch_gemm_paper(const GemmPaperArgs& a, hipStream_t s);
 size_t paper_workspace_bytes(int64_t rows, int64_t cols);
 hipError_t launch_paper(const PaperArgs& a, hipStream_t s);
 

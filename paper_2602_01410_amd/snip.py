@@ -28,7 +28,12 @@ EXPORTS = ("snip_qtensor_code_bytes", "snip_qtensor_scale_bytes", "snip_qtensor_
            "snip_gemm_workspace_bytes", "snip_gemm_fwd_norm", "snip_gemm_dgrad_norm", "snip_gemm_wgrad_norm",
            "snip_loss_divergence", "snip_quantize_sr_fp4", "snip_adamw_sensitivity", "snip_weight_divergence",
            "snip_paper_scale_bytes", "snip_paper_workspace_bytes", "snip_quantize_paper",
-           "snip_quant_error_stats_paper")
+           "snip_quant_error_stats_paper", "snip_gemm_paper")
+
+
+class _PTensorC(ctypes.Structure):
+    _fields_ = [("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("rows", ctypes.c_int64),
+                ("cols", ctypes.c_int64), ("fmt", ctypes.c_int32), ("group", ctypes.c_int32)]
 
 
 class SnipError(RuntimeError):
@@ -85,6 +90,8 @@ def _lib():
         lib.snip_quantize_paper.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp, vp]
         lib.snip_quant_error_stats_paper.restype = ci
         lib.snip_quant_error_stats_paper.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, sz, vp]
+        lib.snip_gemm_paper.restype = ci
+        lib.snip_gemm_paper.argtypes = [ctypes.POINTER(_PTensorC), ctypes.POINTER(_PTensorC), vp, i64, ci, vp]
         cf, cd = ctypes.c_float, ctypes.c_double
         lib.snip_adamw_sensitivity.restype = ci
         lib.snip_adamw_sensitivity.argtypes = [vp, vp, vp, ci, i64, cf, cf, cf, vp, vp, sz, vp]
@@ -226,6 +233,23 @@ def snip_quantize_paper(x: torch.Tensor, fmt: int, axis: int = ROW, group: int =
     _check(_lib().snip_quantize_paper(ptr, rows, cols, ld, fmt, axis, group, codes.data_ptr() if codes.numel() else None,
                                       scales.data_ptr() if scales.numel() else None, _stream(stream)), "snip_quantize_paper")
     return codes, scales
+
+
+def snip_gemm_paper(a_codes, a_scales, a_fmt, a_group, b_codes, b_scales, b_fmt, b_group, out=None,
+                    out_dtype=OUT_BF16, stream=None) -> torch.Tensor:
+    """C = dequant(A) dequant(B)^T for operands from snip_quantize_paper (stored orientation, uint8 codes)."""
+    def pt(codes, scales, fmt, group):
+        rows = codes.shape[0]
+        cols = codes.shape[1] if fmt == FP8 else codes.shape[1] * 2
+        return _PTensorC(codes.data_ptr() if codes.numel() else None, scales.data_ptr() if scales.numel() else None,
+                         rows, cols, fmt, group)
+    pa, pb = pt(a_codes, a_scales, a_fmt, a_group), pt(b_codes, b_scales, b_fmt, b_group)
+    if out is None:
+        out = torch.empty((pa.rows, pb.rows), dtype=torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32,
+                          device=a_codes.device)
+    _check(_lib().snip_gemm_paper(ctypes.byref(pa), ctypes.byref(pb), out.data_ptr(), out.stride(0), out_dtype,
+                                  _stream(stream)), "snip_gemm_paper")
+    return out
 
 
 def snip_quant_error_stats_paper(x: torch.Tensor, axis: int = ROW, group: int = TILE_1x128,
