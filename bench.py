@@ -180,6 +180,22 @@ def next_rows(cfg, layer, snip, wl, reps=10):
         out[f"sr_quantize_{tag}_gbps"] = rate(lambda: snip.snip_quantize_sr_fp4(dy, axis, seed=1, out=q), qbytes)
         out[f"rne_quantize_{tag}_gbps"] = rate(lambda: snip.snip_quantize(dy, snip.FP4, axis, out=q), qbytes)
         del q
+    # the paper's own recipe: 1x128 tiles with real-valued scales on the same gradient, both axes, FP4 and FP8;
+    # its statistics; and the software-scaled GEMM (tiles x 128x128 blocks) on the first linear's forward shapes
+    T, B = snip.TILE_1x128, snip.BLOCK_128x128
+    pws = torch.empty(int(snip._lib().snip_paper_workspace_bytes(dy.shape[0], dy.shape[1])), dtype=torch.uint8, device="cuda")
+    pst = snip.alloc_stats()
+    for axis, tag in ((snip.ROW, "row"), (snip.COL, "col")):
+        out[f"paper_tile_quantize_fp4_{tag}_gbps"] = rate(lambda: snip.snip_quantize_paper(dy, snip.FP4, axis, T), qbytes)
+        out[f"paper_tile_stats_{tag}_gbps"] = rate(lambda: snip.snip_quant_error_stats_paper(dy, axis, T, out=pst, workspace=pws),
+                                                   dy.numel() * 2)
+    l0 = cfg.linears[0]
+    x0, w0 = layer.src[("X", l0.x_group)], layer.src[("W", l0.name)]
+    y0 = torch.empty((cfg.M, l0.N), dtype=torch.bfloat16, device="cuda")
+    for fmt, tag in ((snip.FP8, "fp8"), (snip.FP4, "fp4")):
+        qa, qb = snip.snip_quantize_paper(x0, fmt, snip.ROW, T), snip.snip_quantize_paper(w0, fmt, snip.ROW, B)
+        out[f"paper_gemm_{tag}_tflops"] = rate(lambda: snip.snip_gemm_paper(*qa, fmt, T, *qb, fmt, B, out=y0),
+                                              2.0 * cfg.M * l0.N * l0.K) / 1e3
     m, v, g = (torch.from_numpy(t).cuda().reshape(-1) for t in wl.make_optimizer_state(cfg, lin.name))
     o = torch.empty(1, dtype=torch.float64, device="cuda")
     out["adamw_sensitivity_gbps"] = rate(lambda: snip.snip_adamw_sensitivity(m, v, g, 0.9, 0.999, 1e-8, out=o, workspace=layer.ws),
