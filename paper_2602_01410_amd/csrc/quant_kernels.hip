@@ -212,6 +212,7 @@ __device__ __forceinline__ unsigned amax8(const uint4& v)
 // ------------------------------------------------------------------------------------------
 constexpr int kSeg = 512;
 constexpr int kUnroll = 4;
+constexpr int kStatUnroll = 8;         // loads in flight per lane in the row statistics kernel
 
 template <int FMT, int RULE, bool STATS, bool SR = false>
 __global__ __launch_bounds__(256) void quant_row_kernel(const uint16_t* __restrict__ x, int rows,
@@ -308,16 +309,16 @@ __global__ __launch_bounds__(256) void stats_row_kernel(const uint16_t* __restri
     for (int row = wave; row < rows; row += nwaves) {
         const uint16_t* xr = x + (int64_t)row * ld;
         float s0 = 0.f, s4 = 0.f, s8 = 0.f;
-        for (int c0 = 0; c0 < cols; c0 += kSeg * kUnroll) {
-            uint4 v[kUnroll];
+        for (int c0 = 0; c0 < cols; c0 += kSeg * kStatUnroll) {
+            uint4 v[kStatUnroll];
 #pragma unroll
-            for (int j = 0; j < kUnroll; ++j) {
+            for (int j = 0; j < kStatUnroll; ++j) {
                 const int col = c0 + j * kSeg + lane * 8;
                 v[j] = make_uint4(0, 0, 0, 0);     // zeros quantize to zero: no contribution
                 if (col < cols) v[j] = *reinterpret_cast<const uint4*>(xr + col);
             }
 #pragma unroll
-            for (int j = 0; j < kUnroll; ++j) {
+            for (int j = 0; j < kStatUnroll; ++j) {
                 const unsigned am = quad_max(amax8(v[j]));
                 const unsigned b8 = scale_byte<kFP8, RULE>(am), b4 = scale_byte<kFP4, RULE>(am);
                 const float sc8 = scale_operand(b8), sc4 = scale_operand(b4);

@@ -51,7 +51,10 @@ def test_stats_zero_on_representable_and_match_fused():
     vals *= 2.0 ** rng.integers(-8, 8, size=(64, 1))
     bits = wl.f32_to_bf16_bits(vals.astype(np.float32))
     got, _ = run(snip, bits, oracle.ROW, oracle.NO_OVERFLOW, per_line=False)
-    assert got[0] == np.sum(vals ** 2) and got[1] == 0.0 and got[2] == 0.0
+    # the error norms are exactly zero; the norm of x itself is an fp32 sum over rows of very different
+    # magnitude, so it is held to the tolerance of the statistics, not to equality
+    assert got[1] == 0.0 and got[2] == 0.0
+    assert got[0] == pytest.approx(np.sum(vals ** 2), rel=TOL)
     # fused (quantize + stats) equals stand-alone for the chosen format
     bits2 = wl.f32_to_bf16_bits(rng.standard_normal((256, 512)).astype(np.float32))
     alone, _ = run(snip, bits2, oracle.COL, oracle.NO_OVERFLOW, per_line=False)
