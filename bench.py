@@ -24,7 +24,7 @@ import torch
 PEAK = {"fp4": 10.1e15, "fp8": 5.0e15, "hbm": 8.0e12}
 # L2-miss-side bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated against a copy kernel), measured with
 # rocprofv3 --pmc on this command; see profiles/hbm_traffic_config4_mix50.md.  Keyed by (config, plan, kernel).
-MEASURED_TRAFFIC = {(4, "mix50", "gemm_fast_kernel<fp4,fp4>"): 539.3e6}
+MEASURED_TRAFFIC = {(4, "mix50", "gemm_fast_kernel<fp4,fp4>"): 542.1e6}
 KERNEL_NAME = {(0, 0): "gemm_fast_kernel<fp8,fp8>", (1, 1): "gemm_fast_kernel<fp4,fp4>",
                (0, 1): "gemm_fast_kernel<fp8,fp4>", (1, 0): "gemm_fast_kernel<fp4,fp8>"}
 
