@@ -43,7 +43,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        # SNIP_ORACLE_LIB: an alternative build of this same source (the mutation test of the pins uses it
+        # to load copies with a planted mistake); unset in every other use
+        lib = ctypes.CDLL(os.environ.get("SNIP_ORACLE_LIB") or build())
         i64, dbl, ci, u16 = ctypes.c_int64, ctypes.c_double, ctypes.c_int, ctypes.c_uint16
         vp = ctypes.c_void_p
         lib.oracle_bf16_to_f64.restype = dbl
