@@ -319,6 +319,7 @@ __global__ __launch_bounds__(256) void stats_row_kernel(const uint16_t* __restri
             }
 #pragma unroll
             for (int j = 0; j < kStatUnroll; ++j) {
+                if (c0 + j * kSeg >= cols) break;                    // wave-uniform: the row has no such segment
                 const unsigned am = quad_max(amax8(v[j]));
                 const unsigned b8 = scale_byte<kFP8, RULE>(am), b4 = scale_byte<kFP4, RULE>(am);
                 const float sc8 = scale_operand(b8), sc4 = scale_operand(b4);
