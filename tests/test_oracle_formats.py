@@ -177,3 +177,23 @@ def test_scale_special_blocks():
     assert oracle.scale_byte(FP4, NO_OVERFLOW, 6.5) == 128
     assert oracle.scale_byte(FP4, FLOOR, 7.5) == 127
     assert oracle.scale_byte(FP4, NO_OVERFLOW, 1.0) == 127 - 2
+
+
+def _golden(name):
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
+    return [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+
+
+def test_element_values_from_the_mx_specification():
+    """Decode (and encode back) against the value table kept under tests/golden/."""
+    import math
+    for fmt_name, code, value in _golden("mx_element_values.txt"):
+        fmt = oracle.FP4 if fmt_name == "fp4" else oracle.FP8
+        got = oracle.decode(fmt, int(code, 16))
+        if value == "nan":
+            assert math.isnan(got)
+            continue
+        want = float(value)
+        assert got == want and math.copysign(1.0, got) == math.copysign(1.0, want), (fmt_name, code)
+        assert oracle.encode_rne(fmt, want) == int(code, 16)
