@@ -129,43 +129,56 @@ __device__ __forceinline__ void threefry2x32_20(unsigned c0, unsigned c1, unsign
     o0 = x0; o1 = x1;
 }
 
-// One element: bf16 value in the upper half of `fbits`, scale byte, random byte -> 4-bit code.
-// The grid spacing is 0.5 below 2, 1 in [2, 4) and 2 from 4 on, so with Ec = clamp(exponent of |v|, 0, 2)
-// and k = floor(|v| * 2^(9 - Ec)) the lower neighbour has code (k >> 8) + 2 Ec and floor(256 p) = k & 255.
-// v_ldexp_f32 scales exactly; a scaled magnitude too small for fp32 gives k = 0 like the exact value.
-__device__ __forceinline__ unsigned sr_code(unsigned fbits, unsigned byte, unsigned rnd)
-{
-    const int ex = (int)((fbits >> 23) & 0xFFu) - (int)byte;           // exponent of |v| (garbage-free: clamped next)
-    const int ec = ex < 0 ? 0 : (ex > 2 ? 2 : ex);
-    const float a = __builtin_ldexpf(__uint_as_float(fbits & 0x7FFFFFFFu), 136 - (int)byte - ec);
-    const unsigned k = (unsigned)a;                                     // truncation; |v| < 8 keeps k < 1024
-    unsigned code = (k >> 8) + 2u * (unsigned)ec + (rnd < (k & 0xFFu) ? 1u : 0u);
-    code = code > 7u ? 7u : code;
-    return code | ((fbits >> 28) & 8u);
-}
+// The rule is carried out by gfx950's stochastic-rounding conversion v_cvt_scalef32_sr_pk_fp4_f32.  What that
+// instruction does was established on the hardware for every bf16 magnitude from 2^-12 to 6 (both signs)
+// against 256 seeds per operand slot: for the first element of its pair it adds bits [31:10] of the seed
+// to the 22 mantissa bits that FP4 drops (denormalised below 1) and rounds up on a carry, so with a seed
+// R << 24 it rounds up iff floor(256 p) + R >= 256 -- the rule above with R = 255 - rnd.  The second
+// element of a pair takes the seed shifted by one bit, which would tie its random number to the first
+// one's; every element therefore goes through the first slot of its own instruction (second slot 0.0).
+// Bits below the top eight of the seed must be zero, or they could carry into the comparison.
+// The instruction is written as inline assembly: it replaces one byte of its destination and keeps the
+// other three, and the compiler's builtin for it does not tie the destination to the previous value.
+typedef float float2_t_sr __attribute__((ext_vector_type(2)));
+#define SNIP_SR_CVT(dst, src, seed, sc, OPSEL) \
+    asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, %3" OPSEL : "+v"(dst) : "v"(src), "v"(seed), "v"(sc))
 
 // Four bf16 pairs (8 consecutive stored elements) -> 8 FP4 nibbles with stochastic rounding; r0 holds
-// the random bytes of elements 0-3, r1 those of elements 4-7.
-__device__ __forceinline__ unsigned enc4_sr(const unsigned* w, unsigned byte, unsigned r0, unsigned r1)
+// the random bytes of elements 0-3, r1 those of elements 4-7; sc is the block scale operand.
+__device__ __forceinline__ unsigned enc4_sr(const unsigned* w, float sc, unsigned r0, unsigned r1)
 {
-    unsigned out = 0;
+    const unsigned n0 = ~r0, n1 = ~r1;                      // 255 - rnd in every byte
+    unsigned even = 0, odd = 0;                             // byte i: code of element 2i / 2i+1 in its low nibble
+    float2_t_sr xe[4], xo[4];
+    unsigned se[4], so[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const unsigned rr = i < 2 ? r0 : r1;
-        const unsigned lo = sr_code(w[i] << 16, byte, (rr >> (16 * (i & 1))) & 0xFFu);
-        const unsigned hi = sr_code(w[i] & 0xFFFF0000u, byte, (rr >> (16 * (i & 1) + 8)) & 0xFFu);
-        out |= (lo | (hi << 4)) << (8 * i);
+        const unsigned nn = i < 2 ? n0 : n1;
+        // byte (2i mod 4) resp. (2i+1 mod 4) of nn moved to the top byte, zeros below
+        se[i] = __builtin_amdgcn_perm(nn, 0u, (i & 1) ? 0x060C0C0Cu : 0x040C0C0Cu);
+        so[i] = __builtin_amdgcn_perm(nn, 0u, (i & 1) ? 0x070C0C0Cu : 0x050C0C0Cu);
+        xe[i] = float2_t_sr{__uint_as_float(w[i] << 16), 0.f};
+        xo[i] = float2_t_sr{__uint_as_float(w[i] & 0xFFFF0000u), 0.f};
     }
-    return out;
+    SNIP_SR_CVT(even, xe[0], se[0], sc, "");
+    SNIP_SR_CVT(even, xe[1], se[1], sc, " op_sel:[0,0,1,0]");
+    SNIP_SR_CVT(even, xe[2], se[2], sc, " op_sel:[0,0,0,1]");
+    SNIP_SR_CVT(even, xe[3], se[3], sc, " op_sel:[0,0,1,1]");
+    SNIP_SR_CVT(odd, xo[0], so[0], sc, "");
+    SNIP_SR_CVT(odd, xo[1], so[1], sc, " op_sel:[0,0,1,0]");
+    SNIP_SR_CVT(odd, xo[2], so[2], sc, " op_sel:[0,0,0,1]");
+    SNIP_SR_CVT(odd, xo[3], so[3], sc, " op_sel:[0,0,1,1]");
+    return even | (odd << 4);
 }
+#undef SNIP_SR_CVT
 
 // Codes of the 8 consecutive stored elements that start at stored position e0 (a multiple of 8).
-__device__ __forceinline__ unsigned enc4_sr_at(const unsigned* w, unsigned byte, int64_t e0, uint2 seed)
+__device__ __forceinline__ unsigned enc4_sr_at(const unsigned* w, float sc, int64_t e0, uint2 seed)
 {
     const uint64_t grp = (uint64_t)e0 >> 3;
     unsigned r0, r1;
     threefry2x32_20((unsigned)grp, (unsigned)(grp >> 32), seed.x, seed.y, r0, r1);
-    return enc4_sr(w, byte, r0, r1);
+    return enc4_sr(w, sc, r0, r1);
 }
 
 __device__ __forceinline__ void acc_err(float2_t q, unsigned w, float& s0, float& se, bool want_s0)
@@ -261,7 +274,7 @@ __global__ __launch_bounds__(256) void quant_row_kernel(const uint16_t* __restri
                 if (act[j]) *reinterpret_cast<uint2*>(codes + e0) = make_uint2(c0, c1);
                 if (STATS) err8(w, c0, c1, sc, s0, se, true);
             } else {
-                unsigned c = SR ? enc4_sr_at(w, byte, e0, seed) : enc4(w[0], w[1], w[2], w[3], sc);
+                unsigned c = SR ? enc4_sr_at(w, sc, e0, seed) : enc4(w[0], w[1], w[2], w[3], sc);
                 if (bad) c = 0;
                 if (act[j]) *reinterpret_cast<unsigned*>(codes + (e0 >> 1)) = c;
                 if (STATS) err4(w, c, sc, s0, se, true);
@@ -403,7 +416,7 @@ __device__ __forceinline__ unsigned quant_one_column(const unsigned* w, unsigned
         unsigned c[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            c[k] = SR ? enc4_sr_at(w + 4 * k, byte, e0 + 8 * k, seed)
+            c[k] = SR ? enc4_sr_at(w + 4 * k, sc, e0 + 8 * k, seed)
                       : enc4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3], sc);
             if (bad) c[k] = 0;
         }
