@@ -137,3 +137,29 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(snip, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         snip.workspace_bytes(1, 32)
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 and as C++ without any HIP or torch include, and
+    a C program that only includes it must link against the library and run the host-only calls."""
+    import subprocess
+    snip = lib()
+    src = tmp_path / "use.c"
+    src.write_text(
+        '#include "snip.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        "  snip_layer_plan p = {0, 0, 1, 1, 1, 0}; (void)p;\n"
+        "  if (snip_qtensor_code_bytes(4, 64, SNIP_FP4_E2M1) != 128) return 1;\n"
+        "  if (snip_workspace_bytes(16, 64) == 0) return 2;\n"
+        "  if (snip_loss_divergence(36.0, 36.0, 16, 16.0, 36.0, 4, 9) != 5.0) return 3;\n"
+        "  if (snip_quantize(0, 32, 64, 64, SNIP_FP8_E4M3, SNIP_AXIS_ROW, SNIP_SCALE_NO_OVERFLOW, 0, 0, 0, 0, 0) != SNIP_ERR_NULL) return 4;\n"
+        '  printf("%s\\n", snip_status_string(SNIP_OK));\n  return 0;\n}\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)], check=True)
+    exe = tmp_path / "use"
+    libdir = os.path.dirname(snip.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-lsnip_hip",
+                    "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0 and out.stdout.strip() == "ok", (out.returncode, out.stdout, out.stderr)
