@@ -360,8 +360,8 @@ __global__ __launch_bounds__(256) void stats_row_kernel(const uint16_t* __restri
 // in flight.  The block maximum of a column never leaves the lane.  Rows are re-paired with
 // v_perm so that the conversion instructions pack elements that are adjacent in the
 // transposed output; each lane then stores 32 (FP8) or 16 (FP4) contiguous bytes per column.
-// A wave processes up to four vertically adjacent blocks back to back so that the 128-byte
-// lines of the output are completed within a short time.
+// A wave processes four (FP8) or eight (FP4) vertically adjacent blocks back to back, i.e. exactly one
+// 128-byte line of every stored row, so that no line of the output is written in two pieces.
 // ------------------------------------------------------------------------------------------
 constexpr int kColsPerWave = 128;
 constexpr int kRowBlocksPerUnit = 4;
@@ -389,8 +389,8 @@ __device__ __forceinline__ void load_col_block(const uint16_t* __restrict__ p, i
 }
 
 // Codes of one column's block (32 rows) -> the wave's LDS staging area; returns the scale byte.
-// In LDS the wave keeps a [128 stored rows][ROWB bytes] image of its unit's output (ROWB = 128 FP8,
-// 64 FP4 bytes = 128 source rows); 16-byte chunk c of row r sits at position c ^ ((r >> 1) & (CPR-1)).
+// In LDS the wave keeps a [128 stored rows][ROWB bytes] image of its unit's output (ROWB = 128: 128 source
+// rows of FP8 codes or 256 of FP4 codes); 16-byte chunk c of row r sits at position c ^ ((r >> 1) & (CPR-1)).
 template <int FMT, int RULE, bool STATS, bool SR>
 __device__ __forceinline__ unsigned quant_one_column(const unsigned* w, unsigned am, uint8_t* __restrict__ lds_row,
                                                      int rb_local, int swz, float& s0, float& se,
@@ -438,7 +438,10 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
                                                         float* __restrict__ partials, uint2 seed)
 {
     static_assert(!SR || (FMT == kFP4 && !STATS), "stochastic rounding: FP4, no fused statistics");
-    constexpr int ROWB = FMT == kFP8 ? 128 : 64;     // staged output bytes per stored row (128 source rows)
+    // row blocks per unit: one full 128-byte line of every stored row (128 FP8 / 256 FP4 source rows); the
+    // stochastic variant, bound by VALU work and register count rather than by stores, keeps half lines
+    constexpr int RBU = FMT == kFP8 ? 4 : (SR ? 4 : 8);
+    constexpr int ROWB = RBU * (FMT == kFP8 ? 32 : 16);   // staged output bytes per stored row
     constexpr int CPR = ROWB / 16;
     __shared__ __attribute__((aligned(16))) uint8_t stage[kWavesPerBlock][kColsPerWave * ROWB];
     const int lane = threadIdx.x & 63;
@@ -447,7 +450,7 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
     const int nwaves = gridDim.x * kWavesPerBlock;
     const int ncg = (cols + kColsPerWave - 1) / kColsPerWave;
     const int nrb = rows / kBlock;
-    const int nru = (nrb + kRowBlocksPerUnit - 1) / kRowBlocksPerUnit;
+    const int nru = (nrb + RBU - 1) / RBU;
     const int units = ncg * nru;
     const int64_t out_row_bytes = FMT == kFP8 ? rows : rows / 2;
     float s0 = 0.f, se = 0.f;
@@ -455,21 +458,40 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
         const int ru = u / ncg, cg = u - ru * ncg;
         const int c = cg * kColsPerWave + lane * 2;
         const bool act = c < cols;
-        const int rb0 = ru * kRowBlocksPerUnit;
-        const int nb = min(nrb - rb0, kRowBlocksPerUnit);
+        const int rb0 = ru * RBU;
+        const int nb = min(nrb - rb0, RBU);
         const int swz_lo = lane & (CPR - 1);          // ((2 * lane) >> 1) & (CPR - 1); the odd row shares it
-        unsigned g4_lo = 0, g4_hi = 0;                // the unit's (up to) four scale bytes of the lane's two columns
-        for (int k = 0; k < nb; ++k) {
-            ColBlock b;
-            load_col_block(x + (int64_t)(rb0 + k) * kBlock * ld + c, ld, act, b);
-            const int64_t e0 = (int64_t)c * rows + (int64_t)(rb0 + k) * kBlock;       // stored row = source column
-            const unsigned y0 = quant_one_column<FMT, RULE, STATS, SR>(b.lo, b.am_lo, reg + (2 * lane) * ROWB, k, swz_lo, s0, se, e0, seed);
-            const unsigned y1 = quant_one_column<FMT, RULE, STATS, SR>(b.hi, b.am_hi, reg + (2 * lane + 1) * ROWB, k, swz_lo, s0, se, e0 + rows, seed);
-            g4_lo |= y0 << (8 * k);
-            g4_hi |= y1 << (8 * k);
+        // Four row blocks at a time: their scale bytes of a column form one dword of the row-major array (when
+        // the row length allows it) and exactly one dword of the grouped copy.
+        for (int h = 0; h < RBU / kRowBlocksPerUnit; ++h) {
+            const int nbh = min(nb - h * kRowBlocksPerUnit, kRowBlocksPerUnit);
+            if (nbh <= 0) break;
+            const int rbh = rb0 + h * kRowBlocksPerUnit;
+            unsigned g4_lo = 0, g4_hi = 0;
+            for (int k = 0; k < nbh; ++k) {
+                ColBlock b;
+                load_col_block(x + (int64_t)(rbh + k) * kBlock * ld + c, ld, act, b);
+                const int64_t e0 = (int64_t)c * rows + (int64_t)(rbh + k) * kBlock;       // stored row = source column
+                const int kk = h * kRowBlocksPerUnit + k;
+                const unsigned y0 = quant_one_column<FMT, RULE, STATS, SR>(b.lo, b.am_lo, reg + (2 * lane) * ROWB, kk, swz_lo, s0, se, e0, seed);
+                const unsigned y1 = quant_one_column<FMT, RULE, STATS, SR>(b.hi, b.am_hi, reg + (2 * lane + 1) * ROWB, kk, swz_lo, s0, se, e0 + rows, seed);
+                g4_lo |= y0 << (8 * k);
+                g4_hi |= y1 << (8 * k);
+            }
+            if (act) {
+                uint8_t* s_lo = scales + (int64_t)c * nrb + rbh;
+                if ((nrb & 3) == 0) {
+                    *reinterpret_cast<unsigned*>(s_lo) = g4_lo;
+                    *reinterpret_cast<unsigned*>(s_lo + nrb) = g4_hi;
+                } else {
+                    for (int k = 0; k < nbh; ++k) { s_lo[k] = (uint8_t)(g4_lo >> (8 * k)); s_lo[nrb + k] = (uint8_t)(g4_hi >> (8 * k)); }
+                }
+                if (scales_g4)
+                    *reinterpret_cast<uint2*>(scales_g4 + ((int64_t)(rbh / kRowBlocksPerUnit) * kpitch + c) * 4) = make_uint2(g4_lo, g4_hi);
+            }
         }
         // Codes: read the staged image back row-contiguous and store 16 bytes per lane, so that every store
-        // instruction writes whole 128-byte (FP8) or 64-byte (FP4) runs of 64 / CPR stored rows.
+        // instruction writes whole ROWB-byte runs of 64 / CPR stored rows.
 #pragma unroll
         for (int it = 0; it < kColsPerWave * CPR / 64; ++it) {
             const int idx = it * 64 + lane;
@@ -479,19 +501,6 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
             const int blk = FMT == kFP8 ? chunk >> 1 : chunk;        // row block this chunk belongs to
             if (cc < cols && blk < nb)
                 *reinterpret_cast<uint4*>(codes + (int64_t)cc * out_row_bytes + (int64_t)ru * ROWB + chunk * 16) = v;
-        }
-        // Scales: stored row = source column.  The unit's four bytes of a column are adjacent in the row-major
-        // array (one dword when the row length allows it) and form exactly one dword of the grouped copy.
-        if (act) {
-            uint8_t* s_lo = scales + (int64_t)c * nrb + rb0;
-            if ((nrb & 3) == 0) {
-                *reinterpret_cast<unsigned*>(s_lo) = g4_lo;
-                *reinterpret_cast<unsigned*>(s_lo + nrb) = g4_hi;
-            } else {
-                for (int k = 0; k < nb; ++k) { s_lo[k] = (uint8_t)(g4_lo >> (8 * k)); s_lo[nrb + k] = (uint8_t)(g4_hi >> (8 * k)); }
-            }
-            if (scales_g4)
-                *reinterpret_cast<uint2*>(scales_g4 + ((int64_t)ru * kpitch + c) * 4) = make_uint2(g4_lo, g4_hi);
         }
     }
     if (STATS) {
@@ -653,7 +662,8 @@ static int launch_q(const QuantArgs& a, float* partials, hipStream_t s)
                            g4_pitch(a.rows), partials, seed);
     } else {
         const int64_t nrb = a.rows / kBlock;
-        blocks = balanced_blocks(((a.cols + kColsPerWave - 1) / kColsPerWave) * ((nrb + kRowBlocksPerUnit - 1) / kRowBlocksPerUnit));
+        const int rbu = (FMT == kFP8 || SR) ? kRowBlocksPerUnit : 2 * kRowBlocksPerUnit;       // as in quant_col_kernel
+        blocks = balanced_blocks(((a.cols + kColsPerWave - 1) / kColsPerWave) * ((nrb + rbu - 1) / rbu));
         hipLaunchKernelGGL((quant_col_kernel<FMT, RULE, STATS, SR>), dim3(blocks), dim3(256), 0, s,
                            a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, a.scales_g4,
                            g4_pitch(a.cols), partials, seed);
