@@ -3,7 +3,7 @@
 A step is one pass of the whole path over one Llama-shaped transformer block's seven linear
 layers: every quantization the plan calls for (each distinct (tensor, format, axis) once, with
 the fused error statistics), the 21 GEMMs (fwd, dgrad, wgrad per linear) and the stand-alone
-dual-format statistics pass over every distinct tensor and axis.  Inputs are resident in HBM
+statistics pass (both formats, both block directions, one read) over every distinct tensor.  Inputs are resident in HBM
 before timing starts.  Prints one JSON line.
 """
 from __future__ import annotations
@@ -92,14 +92,15 @@ class Layer:
                                torch.empty((M, l.K), dtype=torch.bfloat16, device=dev), 2 * M * l.N * l.K, (e[2], e[3])))
             self.gjobs.append(("wgrad", pc, need(kdy, e[4], snip.COL), need(kx, e[5], snip.COL),
                                torch.empty((l.N, l.K), dtype=torch.bfloat16, device=dev), 2 * M * l.N * l.K, (e[4], e[5])))
-        self.sjobs = [(key, axis, snip.alloc_stats()) for key in self.src for axis in (snip.ROW, snip.COL)]
+        # statistics pass: both block directions and both formats of every distinct tensor, one read each
+        self.sjobs = [(key, snip.alloc_stats(), snip.alloc_stats()) for key in self.src]
         if output_norms:
             self.gws = torch.empty(max(snip.gemm_workspace_bytes(j[4].shape[0], j[4].shape[1]) for j in self.gjobs),
                                    dtype=torch.uint8, device=dev)
             self.gnorm = [torch.empty(1, dtype=torch.float64, device=dev) for _ in self.gjobs]
         self.flops = sum(j[5] for j in self.gjobs)
         self.q_bytes = sum(self.src[k[0]].numel() * (2 + (1.0 if k[1] == snip.FP8 else 0.5) + 1 / 32) for k, _ in self.qjobs)
-        self.s_bytes = sum(self.src[key].numel() * 2 for key, _, _ in self.sjobs)
+        self.s_bytes = sum(self.src[key].numel() * 2 for key, _, _ in self.sjobs)        # one read per tensor
 
     def step(self, ev=None):
         snip = self.snip
@@ -123,8 +124,9 @@ class Layer:
                 timed(("g", fmts, fl), lambda: fn_norm[name](pc, a, b, out=out, sum_sq=self.gnorm[gi], workspace=self.gws))
             else:
                 timed(("g", fmts, fl), lambda: fn[name](pc, a, b, out=out))
-        for key, axis, st in self.sjobs:
-            timed(("s", axis), lambda: snip.snip_quant_error_stats(self.src[key], axis, out=st, workspace=self.ws))
+        for key, st_row, st_col in self.sjobs:
+            timed(("s",), lambda: snip.snip_quant_error_stats_both(self.src[key], out_row=st_row, out_col=st_col,
+                                                                   workspace=self.ws))
         if ev is not None:
             e = torch.cuda.Event(enable_timing=True)
             e.record()
@@ -291,6 +293,7 @@ def main():
         "gemm_only_tflops": layer.flops / gemm_sec / 1e12,
         "gemm_only_pct_of_plan_peak": 100.0 * layer.flops / gemm_sec / plan_peak,
         "quantize_gbps": layer.q_bytes / q_sec / 1e9, "quantize_pct_hbm": 100.0 * layer.q_bytes / q_sec / PEAK["hbm"],
+        # the statistics kernel reads a tensor once for both block directions: algorithmic bytes = 2 per element
         "stats_gbps": layer.s_bytes / s_sec / 1e9, "stats_pct_hbm": 100.0 * layer.s_bytes / s_sec / PEAK["hbm"],
         "ms_gemm": gemm_sec * 1e3, "ms_quantize": q_sec * 1e3, "ms_stats": s_sec * 1e3,
         # the two accountings of "incl. quantize" without the stand-alone statistics pass

@@ -299,6 +299,17 @@ snip_status snip_quant_error_stats(const void* x, int64_t rows, int64_t cols, in
                                    snip_stats* out, float* per_line,
                                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same statistics for BOTH block directions from one read of the matrix: *out_row is what
+ * snip_quant_error_stats(..., SNIP_AXIS_ROW, ...) delivers and *out_col what SNIP_AXIS_COL
+ * delivers (to the tolerance of the statistics; the sums are grouped differently).  A tensor's
+ * forward operand is blocked along rows and its backward operands down columns (Sec. 2.2), so
+ * this is the complete Step-1 record of a tensor.  rows and cols must both be multiples of 32;
+ * no per-line sums.  workspace: >= snip_workspace_bytes(rows, cols). */
+snip_status snip_quant_error_stats_both(const void* x, int64_t rows, int64_t cols, int64_t ld,
+                                        snip_scale_rule rule, snip_stats* out_row,
+                                        snip_stats* out_col, void* workspace,
+                                        size_t workspace_bytes, void* stream);
+
 const char* snip_status_string(snip_status s);
 
 #ifdef __cplusplus

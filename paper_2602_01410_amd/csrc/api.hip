@@ -344,6 +344,23 @@ snip_status snip_quant_error_stats(const void* x, int64_t rows, int64_t cols, in
     return launch_stats(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
 }
 
+snip_status snip_quant_error_stats_both(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_scale_rule rule,
+                                        snip_stats* out_row, snip_stats* out_col, void* workspace,
+                                        size_t workspace_bytes_, void* stream)
+{
+    snip_status st = check_source(x, rows, cols, ld, SNIP_AXIS_ROW, rule);
+    if (st != SNIP_OK) return st;
+    st = check_source(x, rows, cols, ld, SNIP_AXIS_COL, rule);
+    if (st != SNIP_OK) return st;
+    if (!out_row || !out_col) return SNIP_ERR_NULL;
+    if (!workspace || workspace_bytes_ < workspace_bytes(rows, cols)) return SNIP_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SNIP_ERR_LAYOUT;
+    StatsArgs a;
+    a.x = (const uint16_t*)x; a.rows = rows; a.cols = cols; a.ld = ld; a.axis = SNIP_AXIS_ROW; a.rule = rule;
+    a.stats = (double*)out_row; a.per_line = nullptr; a.workspace = workspace;
+    return launch_stats_both(a, (double*)out_col, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
+}
+
 const char* snip_status_string(snip_status s)
 {
     switch (s) {

@@ -565,6 +565,111 @@ __global__ __launch_bounds__(256) void stats_col_kernel(const uint16_t* __restri
     }
 }
 
+// Statistics for BOTH block directions from one read of the matrix (the complete Step-1 record of a tensor:
+// its forward operands are blocked along rows, its backward ones down columns, Sec. 2.2).
+// Grid and ownership as in stats_col_kernel: a wave owns 128 columns and a range of 32-row blocks; a lane
+// reads two adjacent columns of every row.  The column-direction errors come straight from those registers
+// (a column's block never leaves the lane).  For the row direction the raw 32 x 128 tile goes through the
+// wave's 8 KB of LDS and comes back as eight 16-byte pieces per lane, 8 consecutive elements of one row each,
+// so that four neighbouring lanes hold one 32-element block exactly as in the row kernels.  LDS operations
+// of one wave execute in order, so no barrier is needed between the writes and the reads.
+// partials: [waves][6] = {sum x^2, row err4, row err8, sum x^2, col err4, col err8}.
+template <int RULE>
+__global__ __launch_bounds__(256) void stats_both_kernel(const uint16_t* __restrict__ x, int rows,
+                                                         int cols, int64_t ld, int nsplit,
+                                                         float* __restrict__ partials)
+{
+    __shared__ __attribute__((aligned(16))) unsigned tile[kWavesPerBlock][kBlock * 64];
+    const int lane = threadIdx.x & 63;
+    unsigned* const raw = tile[threadIdx.x >> 6];
+    const int wave_x = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    const int nwaves_x = gridDim.x * kWavesPerBlock;
+    const int split = blockIdx.y;
+    const int ncg = (cols + kColsPerWave - 1) / kColsPerWave;
+    const int nrb = rows / kBlock;
+    const int rb0 = (int)((int64_t)nrb * split / nsplit), rb1 = (int)((int64_t)nrb * (split + 1) / nsplit);
+    float t0 = 0.f, r4 = 0.f, r8 = 0.f, c4 = 0.f, c8 = 0.f;
+    bool bad = false;
+    for (int cg = wave_x; cg < ncg; cg += nwaves_x) {
+        const int c = cg * kColsPerWave + lane * 2;
+        const bool act = c < cols;
+        for (int rb = rb0; rb < rb1; ++rb) {
+            const uint16_t* p = x + (int64_t)rb * kBlock * ld + c;
+            unsigned v[32];
+#pragma unroll
+            for (int i = 0; i < 32; ++i) v[i] = act ? *reinterpret_cast<const unsigned*>(p + (int64_t)i * ld) : 0u;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) raw[i * 64 + lane] = v[i];
+            // ---- column direction ----
+            unsigned m = 0;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) m = pk_max_u16(m, v[i] & 0x7FFF7FFFu);
+            unsigned w[16];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k)
+                    w[k] = __builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], h ? 0x07060302u : 0x05040100u);
+                const unsigned am = h ? m >> 16 : m & 0xFFFFu;
+                const unsigned b8 = scale_byte<kFP8, RULE>(am), b4 = scale_byte<kFP4, RULE>(am);
+                const float sc8 = scale_operand(b8), sc4 = scale_operand(b4);
+                float dummy = 0.f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const unsigned e0 = enc8<RULE>(w[4 * k], w[4 * k + 1], sc8, b8);
+                    const unsigned e1 = enc8<RULE>(w[4 * k + 2], w[4 * k + 3], sc8, b8);
+                    err8(w + 4 * k, e0, e1, sc8, t0, c8, true);
+                    const unsigned e4 = enc4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3], sc4);
+                    err4(w + 4 * k, e4, sc4, dummy, c4, false);
+                }
+                bad |= b8 == 0xFFu;
+            }
+            // ---- row direction: piece j of this lane = elements [8 (idx % 16), +8) of tile row idx / 16 ----
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int idx = j * 64 + lane;
+                const uint4 q = *reinterpret_cast<const uint4*>(raw + (idx >> 4) * 64 + (idx & 15) * 4);
+                const unsigned am = quad_max(amax8(q));
+                const unsigned b8 = scale_byte<kFP8, RULE>(am), b4 = scale_byte<kFP4, RULE>(am);
+                const float sc8 = scale_operand(b8), sc4 = scale_operand(b4);
+                const unsigned ww[4] = {q.x, q.y, q.z, q.w};
+                const unsigned e0 = enc8<RULE>(ww[0], ww[1], sc8, b8), e1 = enc8<RULE>(ww[2], ww[3], sc8, b8);
+                const unsigned e4 = enc4(ww[0], ww[1], ww[2], ww[3], sc4);
+                float dummy = 0.f;
+                err8(ww, e0, e1, sc8, dummy, r8, false);
+                err4(ww, e4, sc4, dummy, r4, false);
+                bad |= b8 == 0xFFu;
+            }
+        }
+    }
+    if (bad) { r4 = c4 = r8 = c8 = __builtin_nanf(""); }     // a non-finite element poisons every error sum of the wave
+    t0 = wave_sum(t0); r4 = wave_sum(r4); r8 = wave_sum(r8); c4 = wave_sum(c4); c8 = wave_sum(c8);
+    if (lane == 0) {
+        float* pp = partials + ((int64_t)split * nwaves_x + wave_x) * 6;
+        pp[0] = t0; pp[1] = r4; pp[2] = r8; pp[3] = t0; pp[4] = c4; pp[5] = c8;
+    }
+}
+
+// Second stage for stats_both_kernel: sums of n partials [n][6] in double, fixed order; out_row and out_col
+// receive three doubles each.
+__global__ __launch_bounds__(1024) void reduce_both_kernel(const float* __restrict__ partials, int n,
+                                                           double* __restrict__ out_row, double* __restrict__ out_col)
+{
+    __shared__ double sh[6][1024];
+    double a[6] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int i = threadIdx.x; i < n; i += 1024)
+        for (int j = 0; j < 6; ++j) a[j] += (double)partials[(size_t)i * 6 + j];
+    for (int j = 0; j < 6; ++j) sh[j][threadIdx.x] = a[j];
+    __syncthreads();
+    for (int st = 512; st > 0; st >>= 1) {
+        if ((int)threadIdx.x < st)
+            for (int j = 0; j < 6; ++j) sh[j][threadIdx.x] += sh[j][threadIdx.x + st];
+        __syncthreads();
+    }
+    if (threadIdx.x < 3) out_row[threadIdx.x] = sh[threadIdx.x][0];
+    else if (threadIdx.x < 6) out_col[threadIdx.x - 3] = sh[threadIdx.x][0];
+}
+
 // Second stage: sum n per-wave partials [n][3] in double, fixed order, one block of 1024 threads.
 // Thread t owns partials 8t .. 8t+7 (and the same window every 8192 partials), read as six float4.
 // mode 0: out = {p0, p1, p2}; mode 1 (fused FP4): out = {p0, p1, NaN}; mode 2 (fused FP8): {p0, NaN, p1}.
@@ -613,7 +718,7 @@ __global__ __launch_bounds__(256) void reduce_lines_kernel(const float* __restri
     per_line[i] = (float)a;
 }
 
-constexpr size_t kPartialBytes = (size_t)kStreamWaves * 3 * sizeof(float);
+constexpr size_t kPartialBytes = (size_t)kStreamWaves * 6 * sizeof(float);      // [waves][3], or [waves][6] for both directions
 
 int col_splits(int64_t rows, int64_t cols, int* gx)
 {
@@ -709,6 +814,26 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
         e = hipGetLastError();
     }
     return e;
+}
+
+hipError_t launch_stats_both(const StatsArgs& a, double* out_col, hipStream_t s)
+{
+    float* partials = (float*)a.workspace;
+    if (a.rows == 0 || a.cols == 0) {
+        hipLaunchKernelGGL(reduce_both_kernel, dim3(1), dim3(1024), 0, s, (const float*)partials, 0, a.stats, out_col);
+        return hipGetLastError();
+    }
+    int gx;
+    const int nsplit = col_splits(a.rows, a.cols, &gx);
+    if (a.rule == 0)
+        hipLaunchKernelGGL((stats_both_kernel<0>), dim3(gx, nsplit), dim3(256), 0, s, a.x, (int)a.rows, (int)a.cols, a.ld, nsplit, partials);
+    else
+        hipLaunchKernelGGL((stats_both_kernel<1>), dim3(gx, nsplit), dim3(256), 0, s, a.x, (int)a.rows, (int)a.cols, a.ld, nsplit, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(reduce_both_kernel, dim3(1), dim3(1024), 0, s, (const float*)partials, gx * kWavesPerBlock * nsplit,
+                       a.stats, out_col);
+    return hipGetLastError();
 }
 
 hipError_t launch_stats(const StatsArgs& a, hipStream_t s)

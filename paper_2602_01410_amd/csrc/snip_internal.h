@@ -92,6 +92,9 @@ hipError_t launch_adamw_sensitivity(const AdamwArgs& a, hipStream_t s);
 hipError_t launch_sum_partials(const float* partials, int64_t n, double* out, hipStream_t s);
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t s);
 hipError_t launch_stats(const StatsArgs& a, hipStream_t s);
+// both block directions from one read: a.stats receives the row-direction record, out_col the column one
+// (a.axis and a.per_line are ignored)
+hipError_t launch_stats_both(const StatsArgs& a, double* out_col, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 bool gemm_fast_eligible(const GemmArgs& a);          // 256x256-tile kernel (gemm_fast.hip)
 hipError_t launch_gemm_fast(const GemmArgs& a, hipStream_t s);

@@ -28,7 +28,7 @@ EXPORTS = ("snip_qtensor_code_bytes", "snip_qtensor_scale_bytes", "snip_qtensor_
            "snip_gemm_workspace_bytes", "snip_gemm_fwd_norm", "snip_gemm_dgrad_norm", "snip_gemm_wgrad_norm",
            "snip_loss_divergence", "snip_quantize_sr_fp4", "snip_adamw_sensitivity", "snip_weight_divergence",
            "snip_paper_scale_bytes", "snip_paper_workspace_bytes", "snip_quantize_paper",
-           "snip_quant_error_stats_paper", "snip_gemm_paper")
+           "snip_quant_error_stats_paper", "snip_gemm_paper", "snip_quant_error_stats_both")
 
 
 class _PTensorC(ctypes.Structure):
@@ -108,6 +108,8 @@ def _lib():
         lib.snip_loss_divergence.argtypes = [ctypes.c_double, ctypes.c_double, i64, ctypes.c_double, ctypes.c_double, i64, i64]
         lib.snip_quant_error_stats.restype = ci
         lib.snip_quant_error_stats.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, vp, sz, vp]
+        lib.snip_quant_error_stats_both.restype = ci
+        lib.snip_quant_error_stats_both.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, sz, vp]
         lib.snip_status_string.restype = ctypes.c_char_p
         lib.snip_status_string.argtypes = [ci]
         _handle = lib
@@ -233,6 +235,23 @@ def snip_quantize_paper(x: torch.Tensor, fmt: int, axis: int = ROW, group: int =
     _check(_lib().snip_quantize_paper(ptr, rows, cols, ld, fmt, axis, group, codes.data_ptr() if codes.numel() else None,
                                       scales.data_ptr() if scales.numel() else None, _stream(stream)), "snip_quantize_paper")
     return codes, scales
+
+
+def snip_quant_error_stats_both(x: torch.Tensor, rule: int = NO_OVERFLOW, out_row: Optional[torch.Tensor] = None,
+                                out_col: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                                stream=None):
+    """Statistics for both block directions from one read; returns (out_row, out_col)."""
+    ptr, rows, cols, ld = _src(x)
+    if out_row is None:
+        out_row = alloc_stats(x.device)
+    if out_col is None:
+        out_col = alloc_stats(x.device)
+    if workspace is None:
+        workspace = alloc_workspace(rows, cols, x.device)
+    _check(_lib().snip_quant_error_stats_both(ptr, rows, cols, ld, rule, out_row.data_ptr(), out_col.data_ptr(),
+                                              workspace.data_ptr(), workspace.numel(), _stream(stream)),
+           "snip_quant_error_stats_both")
+    return out_row, out_col
 
 
 def snip_gemm_paper(a_codes, a_scales, a_fmt, a_group, b_codes, b_scales, b_fmt, b_group, out=None,

@@ -93,6 +93,13 @@ def test_linear_at_full_size(config, plan_name, linear):
         assert float(host(n)[0]) == pytest.approx(stored, rel=5e-6)
     assert float((dw[ns].double() ** 2).sum()) == pytest.approx(oracle.output_sum_sq(want), rel=1e-4)
 
+    # ---- the one-read statistics of both block directions (what the benchmark step calls) agree with the
+    #      per-direction totals checked below ----
+    both_r, both_c = snip.snip_quant_error_stats_both(ddY)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(host(both_r), host(snip.snip_quant_error_stats(ddY, snip.ROW)), rtol=1e-5)
+    np.testing.assert_allclose(host(both_c), host(snip.snip_quant_error_stats(ddY, snip.COL)), rtol=1e-5)
+
     # ---- statistics: sampled lines against the oracle, and total = sum of lines ----
     for t_dev, t_host, axis, idx in ((ddY, dY, snip.ROW, ms), (dX_, X, snip.COL, ks)):
         L = t_host.shape[0] if axis == snip.ROW else t_host.shape[1]

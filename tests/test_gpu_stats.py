@@ -105,3 +105,45 @@ def test_stats_workspace_needs_no_initialisation_and_is_reusable(fill):
                 f = host(st)
                 np.testing.assert_allclose(f[:2], want[:2], rtol=TOL)
                 assert np.isnan(f[2])
+
+
+@pytest.mark.parametrize("rule", [oracle.NO_OVERFLOW, oracle.FLOOR])
+@pytest.mark.parametrize("shape", [(96, 160), (416, 1344), (2048, 4096)])
+def test_stats_both_directions_from_one_read(rule, shape):
+    """snip_quant_error_stats_both against the oracle's two single-direction results."""
+    snip = require_gpu()
+    rng = np.random.default_rng(35)
+    a = rng.standard_t(3, size=shape) * 10.0 ** rng.integers(-3, 3, size=(shape[0], 1))
+    bits = wl.f32_to_bf16_bits(a.astype(np.float32))
+    got_r, got_c = snip.snip_quant_error_stats_both(to_dev(bits), rule)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(host(got_r), oracle.stats(bits, oracle.ROW, rule), rtol=TOL)
+    np.testing.assert_allclose(host(got_c), oracle.stats(bits, oracle.COL, rule), rtol=TOL)
+
+
+def test_stats_both_special_cases():
+    snip = require_gpu()
+    rng = np.random.default_rng(36)
+    # representable values: both directions report zero error
+    vals = rng.choice(np.array([0, .5, 1, 1.5, 2, 3, 4, 6.0]), size=(64, 256)) * rng.choice([-1.0, 1.0], size=(64, 256))
+    bits = wl.f32_to_bf16_bits(vals.astype(np.float32))
+    r, c = snip.snip_quant_error_stats_both(to_dev(bits))
+    torch.cuda.synchronize()
+    assert host(r)[1] == 0.0 and host(r)[2] == 0.0 and host(c)[1] == 0.0 and host(c)[2] == 0.0
+    assert host(r)[0] == pytest.approx(float((vals ** 2).sum()), rel=TOL)
+    # equals the two single-direction calls of the library itself, and is deterministic
+    bits = wl.f32_to_bf16_bits(rng.standard_normal((512, 640)).astype(np.float32))
+    x = to_dev(bits)
+    r1, c1 = snip.snip_quant_error_stats_both(x)
+    r2, c2 = snip.snip_quant_error_stats_both(x)
+    sr = snip.snip_quant_error_stats(x, snip.ROW)
+    sc = snip.snip_quant_error_stats(x, snip.COL)
+    torch.cuda.synchronize()
+    assert torch.equal(r1, r2) and torch.equal(c1, c2)
+    np.testing.assert_allclose(host(r1), host(sr), rtol=1e-6)
+    np.testing.assert_allclose(host(c1), host(sc), rtol=1e-6)
+    # empty
+    e = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    r, c = snip.snip_quant_error_stats_both(e)
+    torch.cuda.synchronize()
+    assert host(r).tolist() == [0.0, 0.0, 0.0] and host(c).tolist() == [0.0, 0.0, 0.0]
