@@ -24,7 +24,7 @@ import torch
 PEAK = {"fp4": 10.1e15, "fp8": 5.0e15, "hbm": 8.0e12}
 # L2-miss-side bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated against a copy kernel), measured with
 # rocprofv3 --pmc on this command; see profiles/hbm_traffic_config4_mix50.md.  Keyed by (config, plan, kernel).
-MEASURED_TRAFFIC = {(4, "mix50", "gemm_fast_kernel<fp4,fp4>"): 542.1e6}
+MEASURED_TRAFFIC = {(4, "mix50", "gemm_fast_kernel<fp4,fp4>"): 541.6e6}
 KERNEL_NAME = {(0, 0): "gemm_fast_kernel<fp8,fp8>", (1, 1): "gemm_fast_kernel<fp4,fp4>",
                (0, 1): "gemm_fast_kernel<fp8,fp4>", (1, 0): "gemm_fast_kernel<fp4,fp8>"}
 
@@ -42,6 +42,8 @@ def parse():
                    help="skip the extra measurements of the stochastic-rounding and AdamW-sensitivity kernels")
     p.add_argument("--output-norms", action="store_true",
                    help="use the GEMM variants that also return the squared Frobenius norm of Y, dX, dW")
+    p.add_argument("--separate-quantize", action="store_true",
+                   help="one quantize call per orientation (two reads of a tensor wanted in both) instead of snip_quantize_both")
     p.add_argument("--microbench", action="store_true",
                    help="run the device microbenchmarks (measured MFMA / HBM / L2 rates) and exit")
     return p.parse_args()
@@ -50,7 +52,7 @@ def parse():
 class Layer:
     """Device tensors, pre-allocated outputs and the launch list of one step."""
 
-    def __init__(self, cfg, plan, snip, wl, output_norms=False):
+    def __init__(self, cfg, plan, snip, wl, output_norms=False, separate_quantize=False):
         self.cfg, self.plan, self.snip = cfg, plan, snip
         self.output_norms = output_norms
         dev = "cuda"
@@ -92,6 +94,17 @@ class Layer:
                                torch.empty((M, l.K), dtype=torch.bfloat16, device=dev), 2 * M * l.N * l.K, (e[2], e[3])))
             self.gjobs.append(("wgrad", pc, need(kdy, e[4], snip.COL), need(kx, e[5], snip.COL),
                                torch.empty((l.N, l.K), dtype=torch.bfloat16, device=dev), 2 * M * l.N * l.K, (e[4], e[5])))
+        # Quantize calls: a tensor wanted with blocks along its rows and down its columns gets both from one call
+        # (the formats may differ); whatever is left over (a second format in one orientation) goes alone.
+        self.qcalls, left = [], list(self.qjobs)
+        while left:
+            j = left.pop(0)
+            mate = next((o for o in left if o[0][0] == j[0][0] and o[0][2] != j[0][2]), None) if not separate_quantize else None
+            if mate is None:
+                self.qcalls.append((j,))
+            else:
+                left.remove(mate)
+                self.qcalls.append((j, mate) if j[0][2] == snip.ROW else (mate, j))
         # statistics pass: both block directions and both formats of every distinct tensor, one read each
         self.sjobs = [(key, snip.alloc_stats(), snip.alloc_stats()) for key in self.src]
         if output_norms:
@@ -99,7 +112,9 @@ class Layer:
                                    dtype=torch.uint8, device=dev)
             self.gnorm = [torch.empty(1, dtype=torch.float64, device=dev) for _ in self.gjobs]
         self.flops = sum(j[5] for j in self.gjobs)
-        self.q_bytes = sum(self.src[k[0]].numel() * (2 + (1.0 if k[1] == snip.FP8 else 0.5) + 1 / 32) for k, _ in self.qjobs)
+        # algorithmic bytes of the quantize calls: one read of the source per call, codes + scales per output
+        self.q_bytes = sum(self.src[call[0][0][0]].numel() * (2 + sum((1.0 if k[1] == snip.FP8 else 0.5) + 1 / 32 for k, _ in call))
+                           for call in self.qcalls)
         self.s_bytes = sum(self.src[key].numel() * 2 for key, _, _ in self.sjobs)        # one read per tensor
 
     def step(self, ev=None):
@@ -115,9 +130,16 @@ class Layer:
                 ev.append((tag, e))
             f()
 
-        for (key, fmt, axis), st in self.qjobs:
-            timed(("q", key[0] == "W"), lambda: snip.snip_quantize(self.src[key], fmt, axis, out=self.q[(key, fmt, axis)],
-                                                                  stats=st, workspace=self.ws))
+        for job in self.qcalls:
+            if len(job) == 2:           # both orientations of one tensor from one read
+                ((key, fr, _), st_r), ((_, fc, _), st_c) = job
+                timed(("q", key[0] == "W"), lambda: snip.snip_quantize_both(
+                    self.src[key], fr, fc, out_row=self.q[(key, fr, snip.ROW)], out_col=self.q[(key, fc, snip.COL)],
+                    stats_row=st_r, stats_col=st_c, workspace=self.ws))
+            else:
+                ((key, fmt, axis), st), = job
+                timed(("q", key[0] == "W"), lambda: snip.snip_quantize(self.src[key], fmt, axis, out=self.q[(key, fmt, axis)],
+                                                                      stats=st, workspace=self.ws))
         fn_norm = {"fwd": snip.snip_gemm_fwd_norm, "dgrad": snip.snip_gemm_dgrad_norm, "wgrad": snip.snip_gemm_wgrad_norm}
         for gi, (name, pc, a, b, out, fl, fmts) in enumerate(self.gjobs):
             if self.output_norms:
@@ -242,7 +264,7 @@ def main():
     plan_name = args.plan or next((p for p in cfg.plans if p.startswith("mix")), cfg.plans[0])
     plan = wl.make_plan(cfg, plan_name)
     torch.cuda.set_device(0)
-    layer = Layer(cfg, plan, snip, wl, args.output_norms)
+    layer = Layer(cfg, plan, snip, wl, args.output_norms, args.separate_quantize)
 
     for _ in range(args.warmup):
         layer.step()
@@ -296,6 +318,7 @@ def main():
         # the statistics kernel reads a tensor once for both block directions: algorithmic bytes = 2 per element
         "stats_gbps": layer.s_bytes / s_sec / 1e9, "stats_pct_hbm": 100.0 * layer.s_bytes / s_sec / PEAK["hbm"],
         "ms_gemm": gemm_sec * 1e3, "ms_quantize": q_sec * 1e3, "ms_stats": s_sec * 1e3,
+        "quantized_tensors": len(layer.qjobs), "quantize_calls": len(layer.qcalls),
         # the two accountings of "incl. quantize" without the stand-alone statistics pass
         "gemm_plus_quantize_tflops": layer.flops / (gemm_sec + q_sec) / 1e12,
         "gemm_plus_quantize_w_amortised_tflops": layer.flops / (gemm_sec + q_sec - qw_sec) / 1e12,

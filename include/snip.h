@@ -138,6 +138,22 @@ snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
                           const snip_qtensor* out, snip_stats* stats,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* Both orientations of one tensor from one pass over it (Sec. 2.2: every GEMM input is quantized
+ * for two GEMMs that contract different axes, e.g. X along its rows for Y = X W^T and down its
+ * columns for dW = dY^T X).  Produces exactly what
+ *     snip_quantize(x, ..., out_row->fmt, SNIP_AXIS_ROW, rule, out_row, stats_row, ...) and
+ *     snip_quantize(x, ..., out_col->fmt, SNIP_AXIS_COL, rule, out_col, stats_col, ...)
+ * produce (codes, scales and grouped scale copies bit for bit; the statistics summed in another
+ * fixed order), reading x from HBM once.  The two formats may differ.
+ *   rows, cols: both multiples of 32; other arguments as for snip_quantize.
+ *   out_row : stored rows x cols;  out_col : stored cols x rows.
+ *   stats_row, stats_col: device, both or neither (SNIP_ERR_NULL for just one). */
+snip_status snip_quantize_both(const void* x, int64_t rows, int64_t cols, int64_t ld,
+                               snip_scale_rule rule, const snip_qtensor* out_row,
+                               const snip_qtensor* out_col, snip_stats* stats_row,
+                               snip_stats* stats_col, void* workspace, size_t workspace_bytes,
+                               void* stream);
+
 /* Quantize to FP4 with stochastic rounding (Sec. 5.1 "Quantization Format and Implementation":
  * FP4 output gradients are rounded probabilistically to the two nearest values).  Arguments,
  * layout, scales (bit-identical to snip_quantize with SNIP_FP4_E2M1) and error behaviour as for

@@ -129,6 +129,38 @@ snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
     return launch_quantize(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
 }
 
+snip_status snip_quantize_both(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_scale_rule rule,
+                               const snip_qtensor* out_row, const snip_qtensor* out_col, snip_stats* stats_row,
+                               snip_stats* stats_col, void* workspace, size_t workspace_bytes_, void* stream)
+{
+    // both orientations: every extent constraint of the two single-orientation calls at once
+    snip_status st = check_source(x, rows, cols, ld, SNIP_AXIS_ROW, rule);
+    if (st == SNIP_OK) st = check_source(x, rows, cols, ld, SNIP_AXIS_COL, rule);
+    if (st != SNIP_OK) return st;
+    if (!out_row || !out_col) return SNIP_ERR_NULL;
+    if ((stats_row == nullptr) != (stats_col == nullptr)) return SNIP_ERR_NULL;
+    const snip_qtensor* outs[2] = {out_row, out_col};
+    for (int i = 0; i < 2; ++i) {
+        const snip_qtensor* o = outs[i];
+        if ((!o->codes || !o->scales) && rows > 0 && cols > 0) return SNIP_ERR_NULL;
+        if (!valid_fmt((snip_fmt)o->fmt)) return SNIP_ERR_FORMAT;
+        if (o->rows != (i == 0 ? rows : cols) || o->cols != (i == 0 ? cols : rows)) return SNIP_ERR_SHAPE;
+        if (!aligned16(o->codes)) return SNIP_ERR_LAYOUT;
+        if (o->scales_g4 && (reinterpret_cast<uintptr_t>(o->scales_g4) & 3u)) return SNIP_ERR_LAYOUT;
+        if (reinterpret_cast<uintptr_t>(o->scales) & 3u) return SNIP_ERR_LAYOUT;
+    }
+    if (stats_row) {
+        if (!workspace || workspace_bytes_ < workspace_bytes(rows, cols)) return SNIP_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return SNIP_ERR_LAYOUT;
+    }
+    QuantBothArgs a;
+    a.x = (const uint16_t*)x; a.rows = rows; a.cols = cols; a.ld = ld; a.rule = rule;
+    a.fmt_r = out_row->fmt; a.codes_r = (uint8_t*)out_row->codes; a.scales_r = out_row->scales; a.g4_r = out_row->scales_g4;
+    a.fmt_c = out_col->fmt; a.codes_c = (uint8_t*)out_col->codes; a.scales_c = out_col->scales; a.g4_c = out_col->scales_g4;
+    a.stats_r = (double*)stats_row; a.stats_c = (double*)stats_col; a.workspace = workspace;
+    return launch_quantize_both(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
+}
+
 snip_status snip_quantize_sr_fp4(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_axis axis,
                                  snip_scale_rule rule, uint64_t seed, const snip_qtensor* out, void* stream)
 {

@@ -371,6 +371,26 @@ struct ColBlock {
     unsigned am_lo, am_hi;     // magnitude bits of each column's block maximum
 };
 
+__device__ __forceinline__ void load_col_raw(const uint16_t* __restrict__ p, int64_t ld, unsigned (&v)[32])
+{
+#pragma unroll
+    for (int i = 0; i < 32; ++i) v[i] = *reinterpret_cast<const unsigned*>(p + (int64_t)i * ld);
+}
+
+__device__ __forceinline__ void pair_col_block(const unsigned (&v)[32], ColBlock& b)
+{
+    unsigned m = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) m = pk_max_u16(m, v[i] & 0x7FFF7FFFu);
+    b.am_lo = m & 0xFFFFu;
+    b.am_hi = m >> 16;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        b.lo[k] = __builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], 0x05040100u);
+        b.hi[k] = __builtin_amdgcn_perm(v[2 * k + 1], v[2 * k], 0x07060302u);
+    }
+}
+
 __device__ __forceinline__ void load_col_block(const uint16_t* __restrict__ p, int64_t ld, bool act, ColBlock& b)
 {
     unsigned v[32];
@@ -507,6 +527,173 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
         s0 = wave_sum(s0);
         se = wave_sum(se);
         if (lane == 0) { partials[wave * 3 + 0] = s0; partials[wave * 3 + 1] = se; partials[wave * 3 + 2] = 0.f; }
+    }
+}
+
+// Both orientations of one tensor from one pass over HBM (Sec. 2.2: X feeds the forward GEMM with blocks along
+// its rows and the weight-gradient GEMM with blocks down its columns; W and dY likewise).  A wave owns the same
+// units as in quant_col_kernel.  For each 32-row x 128-column tile it runs the column-block path above and then
+// reads the tile a second time with the row kernel's lane layout (a lane = 8 consecutive elements, a quad = one
+// block, 16 lanes = the tile's 128 columns of one row, 4 rows per load): those loads hit in cache, the lines
+// having just been fetched by the same wave.  Results are bit-identical to the two single-orientation kernels.
+template <int FMT_R, int FMT_C, int RULE, bool STATS>
+__global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restrict__ x, int rows, int cols, int64_t ld,
+                                                         uint8_t* __restrict__ codes_r, uint8_t* __restrict__ scales_r,
+                                                         uint8_t* __restrict__ g4_r, int64_t kpitch_r,
+                                                         uint8_t* __restrict__ codes_c, uint8_t* __restrict__ scales_c,
+                                                         uint8_t* __restrict__ g4_c, int64_t kpitch_c,
+                                                         float* __restrict__ partials)
+{
+    constexpr int RBU = FMT_C == kFP8 ? 4 : 8;
+    constexpr int ROWB = RBU * (FMT_C == kFP8 ? 32 : 16);
+    constexpr int CPR = ROWB / 16;
+    // Without the statistics the loads of the next tile are issued before the current one is worked on (two sets
+    // of 64 registers); with them the wave is bound by its arithmetic and the plain loop is faster.
+    constexpr bool PREFETCH = !STATS;
+    __shared__ __attribute__((aligned(16))) uint8_t stage[kWavesPerBlock][kColsPerWave * ROWB];
+    const int lane = threadIdx.x & 63;
+    uint8_t* const reg = stage[threadIdx.x >> 6];
+    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    const int nwaves = gridDim.x * kWavesPerBlock;
+    const int ncg = (cols + kColsPerWave - 1) / kColsPerWave;
+    const int nrb = rows / kBlock;
+    const int nru = (nrb + RBU - 1) / RBU;
+    const int units = ncg * nru;
+    const int nblk = cols / kBlock;                       // blocks per row of the row-direction output
+    const int64_t out_row_bytes = FMT_C == kFP8 ? rows : rows / 2;
+    const uint2 no_seed = make_uint2(0, 0);
+    float s0 = 0.f, se_c = 0.f, se_r = 0.f;
+    for (int u = wave; u < units; u += nwaves) {
+        const int ru = u / ncg, cg = u - ru * ncg;
+        const int c = cg * kColsPerWave + lane * 2;
+        const bool act = c < cols;
+        const int rcol = cg * kColsPerWave + (lane & 15) * 8;       // row direction: this lane's 8 columns
+        const bool ract = rcol < cols;
+        const int rb0 = ru * RBU;
+        const int nb = min(nrb - rb0, RBU);
+        const int swz_lo = lane & (CPR - 1);
+        // Tiles of the unit, top to bottom.
+        unsigned g4_lo = 0, g4_hi = 0;
+        // Loads carry no condition (a lane past the last column reads column 0 of the same rows instead and is
+        // zeroed afterwards, under a wave-uniform test), so that all 40 of a tile stay in flight together.
+        const bool ragged = (cg + 1) * kColsPerWave > cols;
+        auto fetch_row = [&](int k, uint4 (&rv)[8]) {
+            const uint16_t* pr = x + (int64_t)((rb0 + k) * kBlock + (lane >> 4)) * ld + (ract ? rcol : 0);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) rv[j] = *reinterpret_cast<const uint4*>(pr + (int64_t)(4 * j) * ld);
+        };
+        auto fetch = [&](int k, unsigned (&cv)[32], uint4 (&rv)[8]) {
+            load_col_raw(x + (int64_t)(rb0 + k) * kBlock * ld + (act ? c : 0), ld, cv);
+            fetch_row(k, rv);
+        };
+        auto work = [&](int k, unsigned (&cv)[32], uint4 (&rv)[8]) {
+            if (ragged) {
+#pragma unroll
+                for (int i = 0; i < 32; ++i) cv[i] = act ? cv[i] : 0u;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) rv[j] = ract ? rv[j] : make_uint4(0, 0, 0, 0);
+            }
+            // ---- column direction
+            ColBlock b;
+            pair_col_block(cv, b);
+            const unsigned y0 = quant_one_column<FMT_C, RULE, STATS, false>(b.lo, b.am_lo, reg + (2 * lane) * ROWB, k, swz_lo, s0, se_c, 0, no_seed);
+            const unsigned y1 = quant_one_column<FMT_C, RULE, STATS, false>(b.hi, b.am_hi, reg + (2 * lane + 1) * ROWB, k, swz_lo, s0, se_c, 0, no_seed);
+            g4_lo |= y0 << (8 * (k & 3));
+            g4_hi |= y1 << (8 * (k & 3));
+            if ((k & 3) == 3 || k == nb - 1) {
+                // four row blocks done: their scale bytes of a column are one dword of the row-major array (when
+                // the row length allows it) and exactly one dword of the grouped copy
+                const int rbh = rb0 + (k & ~3);
+                if (act) {
+                    uint8_t* s_lo = scales_c + (int64_t)c * nrb + rbh;
+                    if ((nrb & 3) == 0) {
+                        *reinterpret_cast<unsigned*>(s_lo) = g4_lo;
+                        *reinterpret_cast<unsigned*>(s_lo + nrb) = g4_hi;
+                    } else {
+                        for (int i = 0; i <= (k & 3); ++i) { s_lo[i] = (uint8_t)(g4_lo >> (8 * i)); s_lo[nrb + i] = (uint8_t)(g4_hi >> (8 * i)); }
+                    }
+                    if (g4_c)
+                        *reinterpret_cast<uint2*>(g4_c + ((int64_t)(rbh / kRowBlocksPerUnit) * kpitch_c + c) * 4) = make_uint2(g4_lo, g4_hi);
+                }
+                g4_lo = 0; g4_hi = 0;
+            }
+            // ---- row direction
+            const int row0 = (rb0 + k) * kBlock + (lane >> 4);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int row = row0 + 4 * j;
+                const unsigned am = quad_max(amax8(rv[j]));
+                const unsigned byte = scale_byte<FMT_R, RULE>(am);
+                const float sc = scale_operand(byte);
+                const bool bad = byte == 0xFFu;
+                const unsigned w[4] = {rv[j].x, rv[j].y, rv[j].z, rv[j].w};
+                const int64_t e0 = (int64_t)row * cols + rcol;
+                float unused = 0.f;
+                if (FMT_R == kFP8) {
+                    unsigned c0 = enc8<RULE>(w[0], w[1], sc, byte), c1 = enc8<RULE>(w[2], w[3], sc, byte);
+                    if (bad) { c0 = 0; c1 = 0; }
+                    if (ract) *reinterpret_cast<uint2*>(codes_r + e0) = make_uint2(c0, c1);
+                    if (STATS) err8(w, c0, c1, sc, unused, se_r, false);
+                } else {
+                    unsigned c4 = enc4(w[0], w[1], w[2], w[3], sc);
+                    if (bad) c4 = 0;
+                    if (ract) *reinterpret_cast<unsigned*>(codes_r + (e0 >> 1)) = c4;
+                    if (STATS) err4(w, c4, sc, unused, se_r, false);
+                }
+                // the four block bytes of this row's 128-column group: one dword of the grouped copy and,
+                // when rows hold a whole number of groups, of the row-major array too
+                const unsigned p1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)byte, 0x104, 0xF, 0xF, true);   // lane + 4
+                const unsigned p2 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)byte, 0x108, 0xF, 0xF, true);   // lane + 8
+                const unsigned p3 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)byte, 0x10C, 0xF, 0xF, true);   // lane + 12
+                const unsigned d = byte | (p1 << 8) | (p2 << 16) | (p3 << 24);
+                if (ract && (lane & 15) == 0) {
+                    if ((nblk & 3) == 0) *reinterpret_cast<unsigned*>(scales_r + (int64_t)row * nblk + cg * 4) = d;
+                    if (g4_r) *reinterpret_cast<unsigned*>(g4_r + ((int64_t)cg * kpitch_r + row) * 4) = d;
+                }
+                if ((nblk & 3) != 0 && ract && (lane & 3) == 0)
+                    scales_r[(int64_t)row * nblk + (rcol >> 5)] = (uint8_t)byte;
+            }
+        };
+        if (PREFETCH) {
+            unsigned cv0[32], cv1[32];
+            uint4 rv0[8], rv1[8];
+            fetch(0, cv0, rv0);
+            for (int k = 0; k < nb; k += 2) {
+                if (k + 1 < nb) fetch(k + 1, cv1, rv1);
+                work(k, cv0, rv0);
+                if (k + 1 < nb) {
+                    if (k + 2 < nb) fetch(k + 2, cv0, rv0);
+                    work(k + 1, cv1, rv1);
+                }
+            }
+        } else {
+            for (int k = 0; k < nb; ++k) {
+                unsigned cv[32];
+                uint4 rv[8];
+                fetch(k, cv, rv);
+                work(k, cv, rv);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < kColsPerWave * CPR / 64; ++it) {
+            const int idx = it * 64 + lane;
+            const int row = idx / CPR, chunk = idx % CPR;
+            const uint4 q = *reinterpret_cast<const uint4*>(reg + row * ROWB + ((chunk ^ ((row >> 1) & (CPR - 1))) * 16));
+            const int cc = cg * kColsPerWave + row;
+            const int blk = FMT_C == kFP8 ? chunk >> 1 : chunk;
+            if (cc < cols && blk < nb)
+                *reinterpret_cast<uint4*>(codes_c + (int64_t)cc * out_row_bytes + (int64_t)ru * ROWB + chunk * 16) = q;
+        }
+    }
+    if (STATS) {
+        s0 = wave_sum(s0);
+        se_r = wave_sum(se_r);
+        se_c = wave_sum(se_c);
+        if (lane == 0) {
+            float* p = partials + wave * 6;
+            p[0] = s0; p[1] = FMT_R == kFP4 ? se_r : 0.f; p[2] = FMT_R == kFP8 ? se_r : 0.f;
+            p[3] = s0; p[4] = FMT_C == kFP4 ? se_c : 0.f; p[5] = FMT_C == kFP8 ? se_c : 0.f;
+        }
     }
 }
 
@@ -653,7 +840,8 @@ __global__ __launch_bounds__(256) void stats_both_kernel(const uint16_t* __restr
 // Second stage for stats_both_kernel: sums of n partials [n][6] in double, fixed order; out_row and out_col
 // receive three doubles each.
 __global__ __launch_bounds__(1024) void reduce_both_kernel(const float* __restrict__ partials, int n,
-                                                           double* __restrict__ out_row, double* __restrict__ out_col)
+                                                           double* __restrict__ out_row, double* __restrict__ out_col,
+                                                           int mode_row, int mode_col)
 {
     __shared__ double sh[6][1024];
     double a[6] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
@@ -666,8 +854,14 @@ __global__ __launch_bounds__(1024) void reduce_both_kernel(const float* __restri
             for (int j = 0; j < 6; ++j) sh[j][threadIdx.x] += sh[j][threadIdx.x + st];
         __syncthreads();
     }
-    if (threadIdx.x < 3) out_row[threadIdx.x] = sh[threadIdx.x][0];
-    else if (threadIdx.x < 6) out_col[threadIdx.x - 3] = sh[threadIdx.x][0];
+    // mode 0: all three sums; mode 1 (fused FP4): the FP8 field is NaN; mode 2 (fused FP8): the FP4 field is NaN
+    if (threadIdx.x < 6) {
+        const int f = threadIdx.x % 3;
+        const int mode = threadIdx.x < 3 ? mode_row : mode_col;
+        double* out = threadIdx.x < 3 ? out_row : out_col;
+        const bool absent = (mode == 1 && f == 2) || (mode == 2 && f == 1);
+        if (out) out[f] = absent ? __builtin_nan("") : sh[threadIdx.x][0];
+    }
 }
 
 // Second stage: sum n per-wave partials [n][3] in double, fixed order, one block of 1024 threads.
@@ -816,11 +1010,52 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
     return e;
 }
 
+template <int FMT_R, int FMT_C, int RULE, bool STATS>
+static void launch_qb(const QuantBothArgs& a, float* partials, int blocks, hipStream_t s)
+{
+    hipLaunchKernelGGL((quant_both_kernel<FMT_R, FMT_C, RULE, STATS>), dim3(blocks), dim3(256), 0, s,
+                       a.x, (int)a.rows, (int)a.cols, a.ld, a.codes_r, a.scales_r, a.g4_r, g4_pitch(a.rows),
+                       a.codes_c, a.scales_c, a.g4_c, g4_pitch(a.cols), partials);
+}
+
+hipError_t launch_quantize_both(const QuantBothArgs& a, hipStream_t s)
+{
+    float* partials = (float*)a.workspace;
+    const bool st = a.stats_r != nullptr;
+    const int mode_r = a.fmt_r == kFP4 ? 1 : 2, mode_c = a.fmt_c == kFP4 ? 1 : 2;
+    if (a.rows == 0 || a.cols == 0) {
+        if (st) hipLaunchKernelGGL(reduce_both_kernel, dim3(1), dim3(1024), 0, s, (const float*)partials, 0, a.stats_r, a.stats_c, mode_r, mode_c);
+        return hipGetLastError();
+    }
+    const int64_t nrb = a.rows / kBlock;
+    const int rbu = a.fmt_c == kFP8 ? kRowBlocksPerUnit : 2 * kRowBlocksPerUnit;           // as in quant_both_kernel
+    const int64_t units = ((a.cols + kColsPerWave - 1) / kColsPerWave) * ((nrb + rbu - 1) / rbu);
+    const int blocks = balanced_blocks(units);
+    const int key = (a.fmt_r << 3) | (a.fmt_c << 2) | (a.rule << 1) | (st ? 1 : 0);
+    switch (key) {
+#define SNIP_QB_CASE(FR, FC, RU, ST) case ((FR) << 3) | ((FC) << 2) | ((RU) << 1) | (ST): launch_qb<FR, FC, RU, (ST) != 0>(a, partials, blocks, s); break;
+        SNIP_QB_CASE(0, 0, 0, 0) SNIP_QB_CASE(0, 0, 0, 1) SNIP_QB_CASE(0, 0, 1, 0) SNIP_QB_CASE(0, 0, 1, 1)
+        SNIP_QB_CASE(0, 1, 0, 0) SNIP_QB_CASE(0, 1, 0, 1) SNIP_QB_CASE(0, 1, 1, 0) SNIP_QB_CASE(0, 1, 1, 1)
+        SNIP_QB_CASE(1, 0, 0, 0) SNIP_QB_CASE(1, 0, 0, 1) SNIP_QB_CASE(1, 0, 1, 0) SNIP_QB_CASE(1, 0, 1, 1)
+        SNIP_QB_CASE(1, 1, 0, 0) SNIP_QB_CASE(1, 1, 0, 1) SNIP_QB_CASE(1, 1, 1, 0) SNIP_QB_CASE(1, 1, 1, 1)
+#undef SNIP_QB_CASE
+        default: return hipErrorInvalidValue;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (st) {
+        hipLaunchKernelGGL(reduce_both_kernel, dim3(1), dim3(1024), 0, s, (const float*)partials, blocks * kWavesPerBlock,
+                           a.stats_r, a.stats_c, mode_r, mode_c);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
 hipError_t launch_stats_both(const StatsArgs& a, double* out_col, hipStream_t s)
 {
     float* partials = (float*)a.workspace;
     if (a.rows == 0 || a.cols == 0) {
-        hipLaunchKernelGGL(reduce_both_kernel, dim3(1), dim3(1024), 0, s, (const float*)partials, 0, a.stats, out_col);
+        hipLaunchKernelGGL(reduce_both_kernel, dim3(1), dim3(1024), 0, s, (const float*)partials, 0, a.stats, out_col, 0, 0);
         return hipGetLastError();
     }
     int gx;
@@ -832,7 +1067,7 @@ hipError_t launch_stats_both(const StatsArgs& a, double* out_col, hipStream_t s)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(reduce_both_kernel, dim3(1), dim3(1024), 0, s, (const float*)partials, gx * kWavesPerBlock * nsplit,
-                       a.stats, out_col);
+                       a.stats, out_col, 0, 0);
     return hipGetLastError();
 }
 

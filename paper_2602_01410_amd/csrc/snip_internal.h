@@ -34,6 +34,18 @@ struct QuantArgs {
     uint64_t sr_seed = 0;
 };
 
+// One source matrix quantized in both orientations by one pass (snip_quantize_both).
+struct QuantBothArgs {
+    const uint16_t* x;
+    int64_t rows, cols, ld;
+    int rule;
+    int fmt_r, fmt_c;                        // row-direction output [rows][cols], column-direction output [cols][rows]
+    uint8_t *codes_r, *scales_r, *g4_r;
+    uint8_t *codes_c, *scales_c, *g4_c;
+    double *stats_r, *stats_c;               // both or neither
+    void* workspace;
+};
+
 struct StatsArgs {
     const uint16_t* x;
     int64_t rows, cols, ld;
@@ -91,6 +103,7 @@ hipError_t launch_adamw_sensitivity(const AdamwArgs& a, hipStream_t s);
 // out[0] = sum of partials[0..n) in index order, in double (one workgroup); n may be 0
 hipError_t launch_sum_partials(const float* partials, int64_t n, double* out, hipStream_t s);
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t s);
+hipError_t launch_quantize_both(const QuantBothArgs& a, hipStream_t s);
 hipError_t launch_stats(const StatsArgs& a, hipStream_t s);
 // both block directions from one read: a.stats receives the row-direction record, out_col the column one
 // (a.axis and a.per_line are ignored)

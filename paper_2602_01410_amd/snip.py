@@ -26,7 +26,7 @@ EXPORTS = ("snip_qtensor_code_bytes", "snip_qtensor_scale_bytes", "snip_qtensor_
            "snip_quantize", "snip_gemm_fwd", "snip_gemm_dgrad", "snip_gemm_wgrad",
            "snip_quant_error_stats", "snip_status_string",
            "snip_gemm_workspace_bytes", "snip_gemm_fwd_norm", "snip_gemm_dgrad_norm", "snip_gemm_wgrad_norm",
-           "snip_loss_divergence", "snip_quantize_sr_fp4", "snip_adamw_sensitivity", "snip_weight_divergence",
+           "snip_loss_divergence", "snip_quantize_sr_fp4", "snip_quantize_both", "snip_adamw_sensitivity", "snip_weight_divergence",
            "snip_paper_scale_bytes", "snip_paper_workspace_bytes", "snip_quantize_paper",
            "snip_quant_error_stats_paper", "snip_gemm_paper", "snip_quant_error_stats_both")
 
@@ -80,6 +80,9 @@ def _lib():
             fn.restype = ci
             fn.argtypes = [ctypes.POINTER(_PlanC), ctypes.POINTER(_QTensorC), ctypes.POINTER(_QTensorC),
                            vp, i64, ci, vp, sz, vp]
+        lib.snip_quantize_both.restype = ci
+        lib.snip_quantize_both.argtypes = [vp, i64, i64, i64, ci, ctypes.POINTER(_QTensorC), ctypes.POINTER(_QTensorC),
+                                           vp, vp, vp, ctypes.c_size_t, vp]
         lib.snip_quantize_sr_fp4.restype = ci
         lib.snip_quantize_sr_fp4.argtypes = [vp, i64, i64, i64, ci, ci, ctypes.c_uint64, ctypes.POINTER(_QTensorC), vp]
         lib.snip_paper_scale_bytes.restype = sz
@@ -206,6 +209,28 @@ def snip_quantize(x: torch.Tensor, fmt: int, axis: int = ROW, rule: int = NO_OVE
                                 workspace.numel() if workspace is not None else 0, _stream(stream)),
            "snip_quantize")
     return out
+
+
+def snip_quantize_both(x: torch.Tensor, fmt_row: int, fmt_col: int, rule: int = NO_OVERFLOW,
+                       out_row: Optional[QTensor] = None, out_col: Optional[QTensor] = None,
+                       stats_row: Optional[torch.Tensor] = None, stats_col: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, stream=None):
+    """Row-block and column-block quantization of x from one read; returns (out_row, out_col)."""
+    ptr, rows, cols, ld = _src(x)
+    if out_row is None:
+        out_row = alloc_qtensor(rows, cols, fmt_row, x.device)
+    if out_col is None:
+        out_col = alloc_qtensor(cols, rows, fmt_col, x.device)
+    if stats_row is not None and workspace is None:
+        workspace = alloc_workspace(rows, cols, x.device)
+    qr, qc = out_row.c_struct(), out_col.c_struct()
+    _check(_lib().snip_quantize_both(ptr, rows, cols, ld, rule, ctypes.byref(qr), ctypes.byref(qc),
+                                     stats_row.data_ptr() if stats_row is not None else None,
+                                     stats_col.data_ptr() if stats_col is not None else None,
+                                     workspace.data_ptr() if workspace is not None else None,
+                                     workspace.numel() if workspace is not None else 0, _stream(stream)),
+           "snip_quantize_both")
+    return out_row, out_col
 
 
 def snip_quantize_sr_fp4(x: torch.Tensor, axis: int = ROW, rule: int = NO_OVERFLOW, seed: int = 0,
