@@ -2,9 +2,10 @@
 
 A step is one pass of the whole path over one Llama-shaped transformer block's seven linear
 layers: every quantization the plan calls for (each distinct (tensor, format, axis) once, with
-the fused error statistics), the 21 GEMMs (fwd, dgrad, wgrad per linear) and the stand-alone
-statistics pass (both formats, both block directions, one read) over every distinct tensor.  Inputs are resident in HBM
-before timing starts.  Prints one JSON line.
+the fused error statistics; a tensor wanted in both orientations gets them from one call and one
+read), the 21 GEMMs (fwd, dgrad, wgrad per linear) and the stand-alone statistics pass (both
+formats, both block directions, one read) over every distinct tensor.  Inputs are resident in
+HBM before timing starts.  Prints one JSON line.
 """
 from __future__ import annotations
 

@@ -93,6 +93,22 @@ def test_linear_at_full_size(config, plan_name, linear):
         assert float(host(n)[0]) == pytest.approx(stored, rel=5e-6)
     assert float((dw[ns].double() ** 2).sum()) == pytest.approx(oracle.output_sum_sq(want), rel=1e-4)
 
+    # ---- both orientations from one call, with fused statistics (what the benchmark step calls): the same bytes
+    #      as the single-orientation calls sampled against the oracle above; statistics against the statistics pass ----
+    for t_dev, f_r, f_c, want_r, want_c in ((dX_, fx, wx, xq_r, xq_c), (ddY, gdy, wdy, dyq_r, dyq_c), (dW_, fw, gw, wq_r, wq_c)):
+        st_r, st_c = snip.alloc_stats(), snip.alloc_stats()
+        got_r, got_c = snip.snip_quantize_both(t_dev, f_r, f_c, stats_row=st_r, stats_col=st_c)
+        ref_r, ref_c = snip.snip_quant_error_stats(t_dev, snip.ROW), snip.snip_quant_error_stats(t_dev, snip.COL)
+        torch.cuda.synchronize()
+        for got, want, st, ref, f in ((got_r, want_r, st_r, ref_r, f_r), (got_c, want_c, st_c, ref_c, f_c)):
+            assert torch.equal(got.codes, want.codes) and torch.equal(got.scales, want.scales)
+            same_g4 = torch.equal(got.scales_g4[:, :got.rows], want.scales_g4[:, :want.rows])
+            assert same_g4
+            k = 2 if f == snip.FP8 else 1
+            np.testing.assert_allclose(host(st)[[0, k]], host(ref)[[0, k]], rtol=1e-5)
+            assert np.isnan(host(st)[3 - k])
+        del got_r, got_c
+
     # ---- the one-read statistics of both block directions (what the benchmark step calls) agree with the
     #      per-direction totals checked below ----
     both_r, both_c = snip.snip_quant_error_stats_both(ddY)
