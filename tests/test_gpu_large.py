@@ -137,3 +137,31 @@ def test_gemm_output_beyond_2_31_elements(big, fmt, R):
     # norm of the stored output: chunked sum of squares in double on the device as the reference
     stored = sum(float((y[i:i + 4096].double() ** 2).sum()) for i in range(0, ROWS, 4096))
     assert float(host(nrm)[0]) == pytest.approx(stored, rel=5e-6)
+
+
+@pytest.mark.parametrize("g_bf16", [False, True])
+def test_adamw_sensitivity_beyond_2_31_elements(g_bf16):
+    """n = 2048 copies of a 1048584-element state plus a 5-element tail (2.1475e9 elements): the sum is 2048 times
+    the block's plus the tail's."""
+    snip = require_gpu()
+    B, R, T = 1048584, 2048, 5
+    b1, b2, eps = float(np.float32(0.9)), float(np.float32(0.999)), float(np.float32(1e-8))
+    rng = np.random.default_rng(4343)
+    g = (1e-3 * rng.standard_normal(B)).astype(np.float32)
+    m = (0.3e-3 * rng.standard_normal(B)).astype(np.float32)
+    v = (1e-6 * (0.5 + rng.random(B))).astype(np.float32)
+    if g_bf16:
+        g = torch.from_numpy(g).to(torch.bfloat16).float().numpy()
+    want = R * oracle.adamw_sensitivity_sq(m, v, g, b1, b2, eps) + oracle.adamw_sensitivity_sq(m[:T], v[:T], g[:T], b1, b2, eps)
+
+    def big(a, dtype):
+        t = torch.from_numpy(a).cuda().to(dtype)
+        return torch.cat([t.repeat(R), t[:T]])
+
+    n = R * B + T
+    assert n > 2 ** 31
+    print("snip_adamw_sensitivity", n, "bf16 g" if g_bf16 else "fp32 g", flush=True)
+    out = snip.snip_adamw_sensitivity(big(m, torch.float32), big(v, torch.float32),
+                                      big(g, torch.bfloat16 if g_bf16 else torch.float32), b1, b2, eps)
+    torch.cuda.synchronize()
+    assert float(host(out)[0]) == pytest.approx(want, rel=1e-5)
