@@ -165,3 +165,31 @@ def test_adamw_sensitivity_beyond_2_31_elements(g_bf16):
                                       big(g, torch.bfloat16 if g_bf16 else torch.float32), b1, b2, eps)
     torch.cuda.synchronize()
     assert float(host(out)[0]) == pytest.approx(want, rel=1e-5)
+
+
+def test_stochastic_rounding_positions_beyond_2_31(big):
+    """Random bytes are drawn by stored position: the last stored row of either orientation lies beyond element
+    2^31.  The oracle's per-element functions are composed here for sampled blocks of that row (its whole-tensor
+    routine would need the whole tensor); scales equal those of nearest-even quantization."""
+    snip = require_gpu()
+    bits, x = big
+    seed = 0x1234567887654321
+    for axis, sr, sc in ((snip.ROW, ROWS, COLS), (snip.COL, COLS, ROWS)):
+        print("snip_quantize_sr_fp4", axis, flush=True)
+        q = snip.snip_quantize_sr_fp4(x, axis, seed=seed)
+        torch.cuda.synchronize()
+        r = sr - 1
+        line = rows_of(bits, r, r + 1)[0] if axis == snip.ROW else cols_of(bits, r, r + 1)[:, 0]
+        assert line.shape == (sc,) and r * sc > 2 ** 31
+        _, want_s = oracle.quantize(line[None, :], oracle.FP4, oracle.ROW)
+        assert np.array_equal(host(q.scales[r]), want_s[0])
+        codes = host(q.codes[r])
+        for b in (0, 1, sc // 64, sc // 32 - 1):
+            scale = 2.0 ** (int(want_s[0, b]) - 127)
+            for k in range(32):
+                c = b * 32 + k
+                v = oracle.bf16_to_f64(int(line[c])) / scale
+                want = oracle.encode_sr_fp4(v, oracle.sr_byte(seed, r * sc + c))
+                got = (int(codes[c // 2]) >> (4 * (c % 2))) & 0xF
+                assert got == want, (axis, c)
+        del q
