@@ -150,16 +150,20 @@ __global__ __launch_bounds__(256) void block_scale_kernel(const uint16_t* __rest
         const int br = b / nbc, bc = b - br * nbc;
         const int c = bc * kGroup + lane * 2;
         const int r0 = br * kGroup, r1 = min(r0 + kGroup, rows);
+        // 128 loads in flight, none under a condition: rows past the end repeat the last row (a maximum does not
+        // mind), lanes past the last column read column 0 and are discarded
+        const uint16_t* const base = x + (c < cols ? c : 0);
+        unsigned v[4][32];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int i = 0; i < 32; ++i) v[k][i] = *reinterpret_cast<const unsigned*>(base + (int64_t)min(r0 + k * 32 + i, r1 - 1) * ld);
         unsigned m = 0;
-        if (c < cols) {
-            for (int r = r0; r < r1; r += 32) {
-                unsigned v[32];
 #pragma unroll
-                for (int i = 0; i < 32; ++i) v[i] = r + i < r1 ? *reinterpret_cast<const unsigned*>(x + (int64_t)(r + i) * ld + c) : 0u;
+        for (int k = 0; k < 4; ++k)
 #pragma unroll
-                for (int i = 0; i < 32; ++i) m = pk_max_u16(m, v[i] & 0x7FFF7FFFu);
-            }
-        }
+            for (int i = 0; i < 32; ++i) m = pk_max_u16(m, v[k][i] & 0x7FFF7FFFu);
+        if (c >= cols) m = 0;
         unsigned am = umax(m & 0xFFFFu, m >> 16);
         for (int off = 32; off > 0; off >>= 1) am = umax(am, (unsigned)__shfl_xor((int)am, off, 64));
         if (lane == 0) {
@@ -343,21 +347,35 @@ __global__ __launch_bounds__(256) void paper_col_kernel(const uint16_t* __restri
         const int ru = u / ncg, cg = u - ru * ncg;
         const int c = cg * kColsPerWave + lane * 2;
         const bool act = c < cols;
-        const uint16_t* const base = x + (int64_t)ru * kGroup * ld + c;
+        // The unit's 128 rows of this lane's two columns stay in registers: one read serves the group maximum
+        // and the encoding, and all 128 loads are in flight together.  They carry no condition (a lane past the
+        // last column reads column 0 of the same rows and is zeroed under a wave-uniform test).
+        const uint16_t* const base = x + (int64_t)ru * kGroup * ld + (act ? c : 0);
+        unsigned v[4][32];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int i = 0; i < 32; ++i) v[k][i] = *reinterpret_cast<const unsigned*>(base + (int64_t)(k * 32 + i) * ld);
+        if ((cg + 1) * kColsPerWave > cols) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int i = 0; i < 32; ++i) v[k][i] = act ? v[k][i] : 0u;
+        }
         float s8[2] = {1.f, 1.f}, s4[2] = {1.f, 1.f};
+        unsigned m = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int i = 0; i < 32; ++i) m = pk_max_u16(m, v[k][i] & 0x7FFF7FFFu);
         if (BLOCKS) {
-            const int gidx = cg * nru + ru;              // stored orientation: [column group][row group]
-            if (MODE == 1 || FMT == kFP8) s8[0] = s8[1] = block_scales8[gidx];
-            if (MODE == 1 || FMT == kFP4) s4[0] = s4[1] = block_scales4[gidx];
+            // the unit is one 128 x 128 block: its maximum is the maximum over the wave
+            unsigned bm = umax(m & 0xFFFFu, m >> 16);
+            for (int off = 32; off > 0; off >>= 1) bm = umax(bm, (unsigned)__shfl_xor((int)bm, off, 64));
+            if (MODE == 1 || FMT == kFP8) s8[0] = s8[1] = group_scale<kFP8>(bm);
+            if (MODE == 1 || FMT == kFP4) s4[0] = s4[1] = group_scale<kFP4>(bm);
+            if (MODE == 0 && lane == 0) scales[cg * nru + ru] = FMT == kFP8 ? s8[0] : s4[0];   // stored orientation: [column group][row group]
         } else {
-            unsigned m = 0;
-            for (int k = 0; k < 4; ++k) {
-                unsigned v[32];
-#pragma unroll
-                for (int i = 0; i < 32; ++i) v[i] = act ? *reinterpret_cast<const unsigned*>(base + (int64_t)(k * 32 + i) * ld) : 0u;
-#pragma unroll
-                for (int i = 0; i < 32; ++i) m = pk_max_u16(m, v[i] & 0x7FFF7FFFu);
-            }
             const unsigned am[2] = {m & 0xFFFFu, m >> 16};
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -370,19 +388,22 @@ __global__ __launch_bounds__(256) void paper_col_kernel(const uint16_t* __restri
             }
         }
         const int swz = lane & (CPR - 1);
-        for (int k = 0; k < 4; ++k) {
-            unsigned v[32];
+        float inv8[2], inv4[2];
+        if (MODE == 1) {
 #pragma unroll
-            for (int i = 0; i < 32; ++i) v[i] = act ? *reinterpret_cast<const unsigned*>(base + (int64_t)(k * 32 + i) * ld) : 0u;
+            for (int h = 0; h < 2; ++h) { inv8[h] = __fdiv_rn(1.f, s8[h]); inv4[h] = __fdiv_rn(1.f, s4[h]); }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
             if (MODE == 0) {
-                encode_column<FMT>(v, 0, FMT == kFP8 ? s8[0] : s4[0], reg + (2 * lane) * ROWB, k, swz);
-                encode_column<FMT>(v, 1, FMT == kFP8 ? s8[1] : s4[1], reg + (2 * lane + 1) * ROWB, k, swz);
+                encode_column<FMT>(v[k], 0, FMT == kFP8 ? s8[0] : s4[0], reg + (2 * lane) * ROWB, k, swz);
+                encode_column<FMT>(v[k], 1, FMT == kFP8 ? s8[1] : s4[1], reg + (2 * lane + 1) * ROWB, k, swz);
             } else if (act) {
                 float dummy = 0.f;
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    err_column<kFP8>(v, h, s8[h], __fdiv_rn(1.f, s8[h]), s0, e8, true);
-                    err_column<kFP4>(v, h, s4[h], __fdiv_rn(1.f, s4[h]), dummy, e4, false);
+                    err_column<kFP8>(v[k], h, s8[h], inv8[h], s0, e8, true);
+                    err_column<kFP4>(v[k], h, s4[h], inv4[h], dummy, e4, false);
                 }
             }
         }
@@ -445,7 +466,7 @@ hipError_t launch_paper(const PaperArgs& a, hipStream_t s)
     const size_t nblocks = (size_t)((a.rows + kGroup - 1) / kGroup) * (size_t)((a.cols + kGroup - 1) / kGroup);
     float* bs8 = nullptr;
     float* bs4 = nullptr;
-    if (a.blocks && !empty) {
+    if (a.blocks && !empty && a.axis == 0) {       // the column kernel finds its blocks' maxima itself
         if (stats) { bs8 = partials + 3 * kStreamWaves; bs4 = bs8 + nblocks; }
         else       { bs8 = a.fmt == kFP8 ? a.scales : nullptr; bs4 = a.fmt == kFP4 ? a.scales : nullptr; }   // the output array itself
         hipLaunchKernelGGL(block_scale_kernel, dim3(blocks_for((int64_t)nblocks)), dim3(256), 0, s,
