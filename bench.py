@@ -40,7 +40,8 @@ def parse():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     p.add_argument("--no-next-rows", action="store_true",
-                   help="skip the extra measurements of the stochastic-rounding and AdamW-sensitivity kernels")
+                   help="skip the measurements made after the timed region: per-variant rates of the streaming kernels, "
+                        "stochastic rounding, the paper's own recipe, the AdamW sensitivity")
     p.add_argument("--output-norms", action="store_true",
                    help="use the GEMM variants that also return the squared Frobenius norm of Y, dX, dW")
     p.add_argument("--separate-quantize", action="store_true",
@@ -177,6 +178,51 @@ def graph_replay(layer, steps, warmup):
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / steps * 1e3
     return {"ms_per_step": ms, "value": layer.flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s"}
+
+
+def kernel_variants(cfg, layer, snip, warm=10, reps=50):
+    """Algorithmic GB/s of every streaming-kernel variant on the output gradient of this configuration's largest
+    linear (larger than the 256 MB Infinity Cache for configs 4 and 5): median of `reps` event-to-event intervals
+    after `warm` untimed calls.  Measured after the timed region; not part of `value`."""
+    lin = max(cfg.linears, key=lambda l: l.N * l.K)
+    x = layer.src[("dY", lin.name)]
+    R, C = x.shape
+    n = x.numel()
+
+    def med_gbps(f, nbytes):
+        for _ in range(warm):
+            f()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for i in range(reps):
+            f()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        t = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
+        return round(nbytes / (t[reps // 2] * 1e-3) / 1e9, 1)
+
+    code = {snip.FP8: 1.0, snip.FP4: 0.5}
+    name = {snip.FP8: "fp8", snip.FP4: "fp4"}
+    out = {"tensor": f"dY of '{lin.name}' [{R} x {C}]", "unit": "GB/s of algorithmic bytes", "hbm_peak_gbps": PEAK["hbm"] / 1e9}
+    st, st2 = snip.alloc_stats(), snip.alloc_stats()
+    for fmt in (snip.FP8, snip.FP4):
+        q = {snip.ROW: snip.alloc_qtensor(R, C, fmt), snip.COL: snip.alloc_qtensor(C, R, fmt)}
+        one = n * (2 + code[fmt] + 1 / 32)
+        for axis, tag in ((snip.ROW, "row"), (snip.COL, "col")):
+            out[f"quantize_{tag}_{name[fmt]}"] = med_gbps(lambda: snip.snip_quantize(x, fmt, axis, out=q[axis]), one)
+            out[f"quantize_{tag}_{name[fmt]}_stats"] = med_gbps(
+                lambda: snip.snip_quantize(x, fmt, axis, out=q[axis], stats=st, workspace=layer.ws), one)
+        both = n * (2 + 2 * (code[fmt] + 1 / 32))
+        out[f"quantize_both_{name[fmt]}"] = med_gbps(
+            lambda: snip.snip_quantize_both(x, fmt, fmt, out_row=q[snip.ROW], out_col=q[snip.COL]), both)
+        out[f"quantize_both_{name[fmt]}_stats"] = med_gbps(
+            lambda: snip.snip_quantize_both(x, fmt, fmt, out_row=q[snip.ROW], out_col=q[snip.COL], stats_row=st, stats_col=st2,
+                                            workspace=layer.ws), both)
+        del q
+    for axis, tag in ((snip.ROW, "row"), (snip.COL, "col")):
+        out[f"stats_{tag}"] = med_gbps(lambda: snip.snip_quant_error_stats(x, axis, out=st, workspace=layer.ws), n * 2)
+    out["stats_both"] = med_gbps(lambda: snip.snip_quant_error_stats_both(x, out_row=st, out_col=st2, workspace=layer.ws), n * 2)
+    return out
 
 
 def next_rows(cfg, layer, snip, wl, reps=10):
@@ -332,6 +378,7 @@ def main():
     if not args.no_graph:
         out["hip_graph"] = graph_replay(layer, args.steps, args.warmup)
     if not args.no_next_rows:
+        out["kernel_variants"] = kernel_variants(cfg, layer, snip)
         out["next_rows"] = next_rows(cfg, layer, snip, wl)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, wl)
