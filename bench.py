@@ -46,6 +46,8 @@ def parse():
                    help="use the GEMM variants that also return the squared Frobenius norm of Y, dX, dW")
     p.add_argument("--separate-quantize", action="store_true",
                    help="one quantize call per orientation (two reads of a tensor wanted in both) instead of snip_quantize_both")
+    p.add_argument("--library-reference", action="store_true",
+                   help="time the vendor library's GEMMs beside snip_gemm_fwd on the 7B shapes, print JSON and exit")
     p.add_argument("--microbench", action="store_true",
                    help="run the device microbenchmarks (measured MFMA / HBM / L2 rates) and exit")
     return p.parse_args()
@@ -274,6 +276,59 @@ def next_rows(cfg, layer, snip, wl, reps=10):
     return out
 
 
+def library_reference(snip, reps=20):
+    """Context, not part of the path: the GEMMs of the vendor's library (hipBLASLt through torch.mm and
+    torch._scaled_mm) on the 7B-shaped problems with N(0,1) operands, beside this repository's block-scaled kernels
+    on the same shapes and data.  A kind the installed library does not support is reported as null."""
+    torch.manual_seed(0)
+
+    def tflops(f, flop):
+        try:
+            for _ in range(3):
+                f()
+        except Exception:
+            return None
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            f()
+        b.record()
+        torch.cuda.synchronize()
+        return round(flop / (a.elapsed_time(b) * 1e-3 / reps) / 1e12, 1)
+
+    rows = []
+    for M, N, K in ((16384, 4096, 4096), (16384, 11008, 4096), (4096, 4096, 16384), (16384, 4096, 11008)):
+        flop = 2.0 * M * N * K
+        x, w = torch.randn(M, K, device="cuda"), torch.randn(N, K, device="cuda")
+        xb, wb = x.bfloat16(), w.bfloat16()
+        r = {"M": M, "N": N, "K": K, "unit": "TFLOP/s"}
+        r["library_bf16"] = tflops(lambda: torch.mm(xb, wb.t()), flop)
+        x8, w8 = x.to(torch.float8_e4m3fn), w.to(torch.float8_e4m3fn)
+        one = torch.ones((), device="cuda")
+        r["library_fp8_one_scale_per_tensor"] = tflops(
+            lambda: torch._scaled_mm(x8, w8.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16), flop)
+        try:
+            e8 = torch.float8_e8m0fnu
+            sa = torch.full((M, K // 32), 127, dtype=torch.uint8, device="cuda").view(e8)
+            sb = torch.full((N, K // 32), 127, dtype=torch.uint8, device="cuda").view(e8)
+            r["library_fp8_e8m0_blocks_of_32"] = tflops(
+                lambda: torch._scaled_mm(x8, w8.t(), scale_a=sa, scale_b=sb, out_dtype=torch.bfloat16), flop)
+            x4 = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda").view(torch.float4_e2m1fn_x2)
+            w4 = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device="cuda").view(torch.float4_e2m1fn_x2)
+            r["library_fp4_e8m0_blocks_of_32"] = tflops(
+                lambda: torch._scaled_mm(x4, w4.t(), scale_a=sa, scale_b=sb, out_dtype=torch.bfloat16), flop)
+        except Exception:
+            r["library_fp8_e8m0_blocks_of_32"] = r["library_fp4_e8m0_blocks_of_32"] = None
+        y = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+        for fmt, tag in ((snip.FP8, "fp8"), (snip.FP4, "fp4")):
+            xq, wq = snip.snip_quantize(xb, fmt, snip.ROW), snip.snip_quantize(wb, fmt, snip.ROW)
+            plan = snip.make_plan((fmt,) * 6)
+            r[f"snip_gemm_{tag}_e8m0_blocks_of_32"] = tflops(lambda: snip.snip_gemm_fwd(plan, xq, wq, out=y), flop)
+        rows.append(r)
+    return rows
+
+
 def cpu_baseline(cfg, wl):
     """The oracle, as it stands, on a bounded sample: the first 256 tokens of the first linear,
     all three GEMMs with their quantizations (fake-quant + fp64 product)."""
@@ -306,6 +361,10 @@ def main():
         exe = os.path.join(ROOT, "paper_2602_01410_amd", "snip_microbench")
         sys.exit(subprocess.run([exe]).returncode)
     from paper_2602_01410_amd import snip, workloads as wl
+    if args.library_reference:
+        snip._lib()
+        print(json.dumps({"library_reference": library_reference(snip)}))
+        return
     snip._lib()
     cfg = wl.CONFIGS[args.config]
     plan_name = args.plan or next((p for p in cfg.plans if p.startswith("mix")), cfg.plans[0])
