@@ -434,6 +434,15 @@ def main():
                      "traffic": MEASURED_TRAFFIC.get((cfg.index, plan_name, KERNEL_NAME[dom])),
                      "launches": dn, "avg_launch_us": dsec / dn * 1e6, "avg_flop_per_launch": dfl / dn},
     }
+    # the same step launched the ordinary way without the per-call events of the timed region (on the small
+    # configurations creating and recording ~60 events per step costs more than the kernels take)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        layer.step()
+    torch.cuda.synchronize()
+    ms_plain = (time.perf_counter() - t1) / args.steps * 1e3
+    out["no_events"] = {"ms_per_step": ms_plain, "value": layer.flops / (ms_plain * 1e-3) / 1e12, "unit": "TFLOP/s"}
     if not args.no_graph:
         out["hip_graph"] = graph_replay(layer, args.steps, args.warmup)
     if not args.no_next_rows:
