@@ -109,6 +109,7 @@ class Layer:
             else:
                 left.remove(mate)
                 self.qcalls.append((j, mate) if j[0][2] == snip.ROW else (mate, j))
+        self.qcalls.sort(key=lambda call: call[0][0][0][0] != "W")        # weights first (stable): their time is reported apart
         # statistics pass: both block directions and both formats of every distinct tensor, one read each
         self.sjobs = [(key, snip.alloc_stats(), snip.alloc_stats()) for key in self.src]
         if output_norms:
@@ -125,13 +126,17 @@ class Layer:
         snip = self.snip
         fn = {"fwd": snip.snip_gemm_fwd, "dgrad": snip.snip_gemm_dgrad, "wgrad": snip.snip_gemm_wgrad}
 
-        # One HIP event in front of every call and one behind the last: a call's duration is the distance
-        # to the next event, on the stream the kernels are launched on.
+        # One HIP event in front of every GEMM call, one wherever the kind of call changes (weight quantizations,
+        # other quantizations, statistics) and one behind the last call: a GEMM's duration, and a group's, is the
+        # distance to the next event, on the stream the kernels are launched on.
+        last = [None]
+
         def timed(tag, f):
-            if ev is not None:
+            if ev is not None and (tag[0] == "g" or tag != last[0]):
                 e = torch.cuda.Event(enable_timing=True)
                 e.record()
                 ev.append((tag, e))
+            last[0] = tag
             f()
 
         for job in self.qcalls:
