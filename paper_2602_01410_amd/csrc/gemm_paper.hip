@@ -71,12 +71,14 @@ __device__ __forceinline__ v8i load_frag(const uint8_t* lds, int row, int g, int
     return f;
 }
 
-// 1 / scale of (row, slab); rows past the end contribute nothing.
-__device__ __forceinline__ float inv_scale(const float* __restrict__ scales, int row, int nrows, int group_rows,
+// Scale of (row, slab) as stored; +infinity for rows past the end, whose reciprocal (the factor used) is zero.
+// The reciprocal is taken one slab later, when the load has landed anyway: a use right after the load would make
+// the wave wait for every load in flight, the next slab's operands included.
+__device__ __forceinline__ float raw_scale(const float* __restrict__ scales, int row, int nrows, int group_rows,
                                            int ng, int slab)
 {
-    if (row >= nrows) return 0.f;
-    return __fdiv_rn(1.f, scales[(int64_t)(group_rows == 1 ? row : row >> 7) * ng + slab]);
+    if (row >= nrows) return __builtin_inff();
+    return scales[(int64_t)(group_rows == 1 ? row : row >> 7) * ng + slab];
 }
 
 template <int FA, int FB, bool OUT_F32>
@@ -112,24 +114,24 @@ __global__ __launch_bounds__(NTHREADS) void gemm_paper_kernel(const uint8_t* __r
     for (int ib = 0; ib < 2; ++ib) arow[ib] = i0 + wm * WM + ib * 32 + r32;
     const int bcol = j0 + (threadIdx.x & (BN - 1));            // the column whose factor this thread fetches
 
+    float sa_n[2] = {raw_scale(a_scales, arow[0], I, a_group, nslab, 0), raw_scale(a_scales, arow[1], I, a_group, nslab, 0)};
+    float sb_n = raw_scale(b_scales, bcol, J, b_group, nslab, 0);
     gload<FA>(ra, a_codes, a_row_bytes, i0, I, 0);
     gload<FB>(rb, b_codes, b_row_bytes, j0, J, 0);
-    float da_n[2] = {inv_scale(a_scales, arow[0], I, a_group, nslab, 0), inv_scale(a_scales, arow[1], I, a_group, nslab, 0)};
-    float db_n = inv_scale(b_scales, bcol, J, b_group, nslab, 0);
 
     for (int s = 0; s < nslab; ++s) {
         __syncthreads();                                       // the previous slab's LDS reads are done
         sstore<FA>(ra, lds_a);
         sstore<FB>(rb, lds_b);
-        if (threadIdx.x < BN) lds_db[s & 1][threadIdx.x] = db_n;
-        const float da[2] = {da_n[0], da_n[1]};
+        if (threadIdx.x < BN) lds_db[s & 1][threadIdx.x] = __fdiv_rn(1.f, sb_n);
+        const float da[2] = {__fdiv_rn(1.f, sa_n[0]), __fdiv_rn(1.f, sa_n[1])};
         __syncthreads();
         if (s + 1 < nslab) {
+            sa_n[0] = raw_scale(a_scales, arow[0], I, a_group, nslab, s + 1);
+            sa_n[1] = raw_scale(a_scales, arow[1], I, a_group, nslab, s + 1);
+            sb_n = raw_scale(b_scales, bcol, J, b_group, nslab, s + 1);
             gload<FA>(ra, a_codes, a_row_bytes, i0, I, (int64_t)(s + 1) * Op<FA>::SB);
             gload<FB>(rb, b_codes, b_row_bytes, j0, J, (int64_t)(s + 1) * Op<FB>::SB);
-            da_n[0] = inv_scale(a_scales, arow[0], I, a_group, nslab, s + 1);
-            da_n[1] = inv_scale(a_scales, arow[1], I, a_group, nslab, s + 1);
-            db_n = inv_scale(b_scales, bcol, J, b_group, nslab, s + 1);
         }
         // the slab's products with unit scales, into a fresh accumulator
         v16f tmp[2][2];
