@@ -138,6 +138,9 @@ snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
                           const snip_qtensor* out, snip_stats* stats,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* Which error sums the fused statistics of snip_quantize_both deliver. */
+typedef enum { SNIP_STATS_CHOSEN_FORMAT = 0, SNIP_STATS_BOTH_FORMATS = 1 } snip_stats_scope;
+
 /* Both orientations of one tensor from one pass over it (Sec. 2.2: every GEMM input is quantized
  * for two GEMMs that contract different axes, e.g. X along its rows for Y = X W^T and down its
  * columns for dW = dY^T X).  Produces exactly what
@@ -147,12 +150,18 @@ snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
  * fixed order), reading x from HBM once.  The two formats may differ.
  *   rows, cols: both multiples of 32; other arguments as for snip_quantize.
  *   out_row : stored rows x cols;  out_col : stored cols x rows.
- *   stats_row, stats_col: device, both or neither (SNIP_ERR_NULL for just one). */
+ *   stats_row, stats_col: device, both or neither (SNIP_ERR_NULL for just one).
+ *   scope   : SNIP_STATS_CHOSEN_FORMAT: as the fused statistics of snip_quantize (the field of the
+ *             format not written is NaN).  SNIP_STATS_BOTH_FORMATS: all three fields, i.e. what
+ *             snip_quant_error_stats_both delivers, out of the same pass: the complete Step-1
+ *             record of a tensor (Sec. 3.1; the ILP needs the error of the option not in use,
+ *             Sec. 4.2) together with its two quantized orientations from one read.  Ignored
+ *             without statistics outputs. */
 snip_status snip_quantize_both(const void* x, int64_t rows, int64_t cols, int64_t ld,
                                snip_scale_rule rule, const snip_qtensor* out_row,
                                const snip_qtensor* out_col, snip_stats* stats_row,
-                               snip_stats* stats_col, void* workspace, size_t workspace_bytes,
-                               void* stream);
+                               snip_stats* stats_col, snip_stats_scope scope, void* workspace,
+                               size_t workspace_bytes, void* stream);
 
 /* Quantize to FP4 with stochastic rounding (Sec. 5.1 "Quantization Format and Implementation":
  * FP4 output gradients are rounded probabilistically to the two nearest values).  Arguments,

@@ -131,8 +131,10 @@ snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
 
 snip_status snip_quantize_both(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_scale_rule rule,
                                const snip_qtensor* out_row, const snip_qtensor* out_col, snip_stats* stats_row,
-                               snip_stats* stats_col, void* workspace, size_t workspace_bytes_, void* stream)
+                               snip_stats* stats_col, snip_stats_scope scope, void* workspace, size_t workspace_bytes_,
+                               void* stream)
 {
+    if (scope != SNIP_STATS_CHOSEN_FORMAT && scope != SNIP_STATS_BOTH_FORMATS) return SNIP_ERR_FORMAT;
     // both orientations: every extent constraint of the two single-orientation calls at once
     snip_status st = check_source(x, rows, cols, ld, SNIP_AXIS_ROW, rule);
     if (st == SNIP_OK) st = check_source(x, rows, cols, ld, SNIP_AXIS_COL, rule);
@@ -158,6 +160,7 @@ snip_status snip_quantize_both(const void* x, int64_t rows, int64_t cols, int64_
     a.fmt_r = out_row->fmt; a.codes_r = (uint8_t*)out_row->codes; a.scales_r = out_row->scales; a.g4_r = out_row->scales_g4;
     a.fmt_c = out_col->fmt; a.codes_c = (uint8_t*)out_col->codes; a.scales_c = out_col->scales; a.g4_c = out_col->scales_g4;
     a.stats_r = (double*)stats_row; a.stats_c = (double*)stats_col; a.workspace = workspace;
+    a.both_formats = scope == SNIP_STATS_BOTH_FORMATS;
     return launch_quantize_both(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
 }
 

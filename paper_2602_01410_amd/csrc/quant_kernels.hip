@@ -536,7 +536,22 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
 // reads the tile a second time with the row kernel's lane layout (a lane = 8 consecutive elements, a quad = one
 // block, 16 lanes = the tile's 128 columns of one row, 4 rows per load): those loads hit in cache, the lines
 // having just been fetched by the same wave.  Results are bit-identical to the two single-orientation kernels.
-template <int FMT_R, int FMT_C, int RULE, bool STATS>
+// Error sum of one column's block (w: its 32 elements as 16 bf16 pairs, am: magnitude bits of its maximum) under
+// the format that is NOT being written; no codes leave the lane.
+template <int FMT, int RULE>
+__device__ __forceinline__ void other_format_error(const unsigned* w, unsigned am, float& se)
+{
+    const unsigned byte = scale_byte<FMT, RULE>(am);
+    const float sc = scale_operand(byte);
+    float unused = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        if (FMT == kFP8) err8(w + 4 * k, enc8<RULE>(w[4 * k], w[4 * k + 1], sc, byte), enc8<RULE>(w[4 * k + 2], w[4 * k + 3], sc, byte), sc, unused, se, false);
+        else             err4(w + 4 * k, enc4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3], sc), sc, unused, se, false);
+    }
+}
+
+template <int FMT_R, int FMT_C, int RULE, int STATS>      // STATS: 0 none, 1 the chosen formats' errors, 2 both formats' errors
 __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restrict__ x, int rows, int cols, int64_t ld,
                                                          uint8_t* __restrict__ codes_r, uint8_t* __restrict__ scales_r,
                                                          uint8_t* __restrict__ g4_r, int64_t kpitch_r,
@@ -549,7 +564,7 @@ __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restr
     constexpr int CPR = ROWB / 16;
     // Without the statistics the loads of the next tile are issued before the current one is worked on (two sets
     // of 64 registers); with them the wave is bound by its arithmetic and the plain loop is faster.
-    constexpr bool PREFETCH = !STATS;
+    constexpr bool PREFETCH = STATS == 0;
     __shared__ __attribute__((aligned(16))) uint8_t stage[kWavesPerBlock][kColsPerWave * ROWB];
     const int lane = threadIdx.x & 63;
     uint8_t* const reg = stage[threadIdx.x >> 6];
@@ -563,6 +578,7 @@ __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restr
     const int64_t out_row_bytes = FMT_C == kFP8 ? rows : rows / 2;
     const uint2 no_seed = make_uint2(0, 0);
     float s0 = 0.f, se_c = 0.f, se_r = 0.f;
+    float so_c = 0.f, so_r = 0.f;                         // STATS == 2: error sums of the format not chosen
     for (int u = wave; u < units; u += nwaves) {
         const int ru = u / ncg, cg = u - ru * ncg;
         const int c = cg * kColsPerWave + lane * 2;
@@ -596,10 +612,14 @@ __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restr
             // ---- column direction
             ColBlock b;
             pair_col_block(cv, b);
-            const unsigned y0 = quant_one_column<FMT_C, RULE, STATS, false>(b.lo, b.am_lo, reg + (2 * lane) * ROWB, k, swz_lo, s0, se_c, 0, no_seed);
-            const unsigned y1 = quant_one_column<FMT_C, RULE, STATS, false>(b.hi, b.am_hi, reg + (2 * lane + 1) * ROWB, k, swz_lo, s0, se_c, 0, no_seed);
+            const unsigned y0 = quant_one_column<FMT_C, RULE, STATS != 0, false>(b.lo, b.am_lo, reg + (2 * lane) * ROWB, k, swz_lo, s0, se_c, 0, no_seed);
+            const unsigned y1 = quant_one_column<FMT_C, RULE, STATS != 0, false>(b.hi, b.am_hi, reg + (2 * lane + 1) * ROWB, k, swz_lo, s0, se_c, 0, no_seed);
             g4_lo |= y0 << (8 * (k & 3));
             g4_hi |= y1 << (8 * (k & 3));
+            if (STATS == 2) {
+                other_format_error<1 - FMT_C, RULE>(b.lo, b.am_lo, so_c);
+                other_format_error<1 - FMT_C, RULE>(b.hi, b.am_hi, so_c);
+            }
             if ((k & 3) == 3 || k == nb - 1) {
                 // four row blocks done: their scale bytes of a column are one dword of the row-major array (when
                 // the row length allows it) and exactly one dword of the grouped copy
@@ -634,11 +654,21 @@ __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restr
                     if (bad) { c0 = 0; c1 = 0; }
                     if (ract) *reinterpret_cast<uint2*>(codes_r + e0) = make_uint2(c0, c1);
                     if (STATS) err8(w, c0, c1, sc, unused, se_r, false);
+                    if (STATS == 2) {
+                        const unsigned bo = scale_byte<kFP4, RULE>(am);
+                        const float sco = scale_operand(bo);
+                        err4(w, enc4(w[0], w[1], w[2], w[3], sco), sco, unused, so_r, false);
+                    }
                 } else {
                     unsigned c4 = enc4(w[0], w[1], w[2], w[3], sc);
                     if (bad) c4 = 0;
                     if (ract) *reinterpret_cast<unsigned*>(codes_r + (e0 >> 1)) = c4;
                     if (STATS) err4(w, c4, sc, unused, se_r, false);
+                    if (STATS == 2) {
+                        const unsigned bo = scale_byte<kFP8, RULE>(am);
+                        const float sco = scale_operand(bo);
+                        err8(w, enc8<RULE>(w[0], w[1], sco, bo), enc8<RULE>(w[2], w[3], sco, bo), sco, unused, so_r, false);
+                    }
                 }
                 // the four block bytes of this row's 128-column group: one dword of the grouped copy and,
                 // when rows hold a whole number of groups, of the row-major array too
@@ -689,10 +719,11 @@ __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restr
         s0 = wave_sum(s0);
         se_r = wave_sum(se_r);
         se_c = wave_sum(se_c);
+        if (STATS == 2) { so_r = wave_sum(so_r); so_c = wave_sum(so_c); }
         if (lane == 0) {
             float* p = partials + wave * 6;
-            p[0] = s0; p[1] = FMT_R == kFP4 ? se_r : 0.f; p[2] = FMT_R == kFP8 ? se_r : 0.f;
-            p[3] = s0; p[4] = FMT_C == kFP4 ? se_c : 0.f; p[5] = FMT_C == kFP8 ? se_c : 0.f;
+            p[0] = s0; p[1] = FMT_R == kFP4 ? se_r : so_r; p[2] = FMT_R == kFP8 ? se_r : so_r;
+            p[3] = s0; p[4] = FMT_C == kFP4 ? se_c : so_c; p[5] = FMT_C == kFP8 ? se_c : so_c;
         }
     }
 }
@@ -1010,7 +1041,7 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
     return e;
 }
 
-template <int FMT_R, int FMT_C, int RULE, bool STATS>
+template <int FMT_R, int FMT_C, int RULE, int STATS>
 static void launch_qb(const QuantBothArgs& a, float* partials, int blocks, hipStream_t s)
 {
     hipLaunchKernelGGL((quant_both_kernel<FMT_R, FMT_C, RULE, STATS>), dim3(blocks), dim3(256), 0, s,
@@ -1022,7 +1053,8 @@ hipError_t launch_quantize_both(const QuantBothArgs& a, hipStream_t s)
 {
     float* partials = (float*)a.workspace;
     const bool st = a.stats_r != nullptr;
-    const int mode_r = a.fmt_r == kFP4 ? 1 : 2, mode_c = a.fmt_c == kFP4 ? 1 : 2;
+    // second stage: which field of each triple is "not computed" (NaN); none when both formats are wanted
+    const int mode_r = a.both_formats ? 0 : (a.fmt_r == kFP4 ? 1 : 2), mode_c = a.both_formats ? 0 : (a.fmt_c == kFP4 ? 1 : 2);
     if (a.rows == 0 || a.cols == 0) {
         if (st) hipLaunchKernelGGL(reduce_both_kernel, dim3(1), dim3(1024), 0, s, (const float*)partials, 0, a.stats_r, a.stats_c, mode_r, mode_c);
         return hipGetLastError();
@@ -1031,13 +1063,15 @@ hipError_t launch_quantize_both(const QuantBothArgs& a, hipStream_t s)
     const int rbu = a.fmt_c == kFP8 ? kRowBlocksPerUnit : 2 * kRowBlocksPerUnit;           // as in quant_both_kernel
     const int64_t units = ((a.cols + kColsPerWave - 1) / kColsPerWave) * ((nrb + rbu - 1) / rbu);
     const int blocks = balanced_blocks(units);
-    const int key = (a.fmt_r << 3) | (a.fmt_c << 2) | (a.rule << 1) | (st ? 1 : 0);
+    const int mode = !st ? 0 : (a.both_formats ? 2 : 1);
+    const int key = (a.fmt_r << 4) | (a.fmt_c << 3) | (a.rule << 2) | mode;
     switch (key) {
-#define SNIP_QB_CASE(FR, FC, RU, ST) case ((FR) << 3) | ((FC) << 2) | ((RU) << 1) | (ST): launch_qb<FR, FC, RU, (ST) != 0>(a, partials, blocks, s); break;
-        SNIP_QB_CASE(0, 0, 0, 0) SNIP_QB_CASE(0, 0, 0, 1) SNIP_QB_CASE(0, 0, 1, 0) SNIP_QB_CASE(0, 0, 1, 1)
-        SNIP_QB_CASE(0, 1, 0, 0) SNIP_QB_CASE(0, 1, 0, 1) SNIP_QB_CASE(0, 1, 1, 0) SNIP_QB_CASE(0, 1, 1, 1)
-        SNIP_QB_CASE(1, 0, 0, 0) SNIP_QB_CASE(1, 0, 0, 1) SNIP_QB_CASE(1, 0, 1, 0) SNIP_QB_CASE(1, 0, 1, 1)
-        SNIP_QB_CASE(1, 1, 0, 0) SNIP_QB_CASE(1, 1, 0, 1) SNIP_QB_CASE(1, 1, 1, 0) SNIP_QB_CASE(1, 1, 1, 1)
+#define SNIP_QB_CASE(FR, FC, RU) \
+        case ((FR) << 4) | ((FC) << 3) | ((RU) << 2) | 0: launch_qb<FR, FC, RU, 0>(a, partials, blocks, s); break; \
+        case ((FR) << 4) | ((FC) << 3) | ((RU) << 2) | 1: launch_qb<FR, FC, RU, 1>(a, partials, blocks, s); break; \
+        case ((FR) << 4) | ((FC) << 3) | ((RU) << 2) | 2: launch_qb<FR, FC, RU, 2>(a, partials, blocks, s); break;
+        SNIP_QB_CASE(0, 0, 0) SNIP_QB_CASE(0, 0, 1) SNIP_QB_CASE(0, 1, 0) SNIP_QB_CASE(0, 1, 1)
+        SNIP_QB_CASE(1, 0, 0) SNIP_QB_CASE(1, 0, 1) SNIP_QB_CASE(1, 1, 0) SNIP_QB_CASE(1, 1, 1)
 #undef SNIP_QB_CASE
         default: return hipErrorInvalidValue;
     }

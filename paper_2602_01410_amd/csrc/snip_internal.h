@@ -43,6 +43,7 @@ struct QuantBothArgs {
     uint8_t *codes_r, *scales_r, *g4_r;
     uint8_t *codes_c, *scales_c, *g4_c;
     double *stats_r, *stats_c;               // both or neither
+    bool both_formats = false;               // statistics: also the error of the format not written
     void* workspace;
 };
 

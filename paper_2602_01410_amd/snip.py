@@ -82,7 +82,7 @@ def _lib():
                            vp, i64, ci, vp, sz, vp]
         lib.snip_quantize_both.restype = ci
         lib.snip_quantize_both.argtypes = [vp, i64, i64, i64, ci, ctypes.POINTER(_QTensorC), ctypes.POINTER(_QTensorC),
-                                           vp, vp, vp, ctypes.c_size_t, vp]
+                                           vp, vp, ci, vp, ctypes.c_size_t, vp]
         lib.snip_quantize_sr_fp4.restype = ci
         lib.snip_quantize_sr_fp4.argtypes = [vp, i64, i64, i64, ci, ci, ctypes.c_uint64, ctypes.POINTER(_QTensorC), vp]
         lib.snip_paper_scale_bytes.restype = sz
@@ -214,8 +214,9 @@ def snip_quantize(x: torch.Tensor, fmt: int, axis: int = ROW, rule: int = NO_OVE
 def snip_quantize_both(x: torch.Tensor, fmt_row: int, fmt_col: int, rule: int = NO_OVERFLOW,
                        out_row: Optional[QTensor] = None, out_col: Optional[QTensor] = None,
                        stats_row: Optional[torch.Tensor] = None, stats_col: Optional[torch.Tensor] = None,
-                       workspace: Optional[torch.Tensor] = None, stream=None):
-    """Row-block and column-block quantization of x from one read; returns (out_row, out_col)."""
+                       workspace: Optional[torch.Tensor] = None, stream=None, both_formats: bool = False):
+    """Row-block and column-block quantization of x from one read; returns (out_row, out_col).  With statistics
+    outputs and both_formats=True they receive the error sums of both formats, not only of the ones written."""
     ptr, rows, cols, ld = _src(x)
     if out_row is None:
         out_row = alloc_qtensor(rows, cols, fmt_row, x.device)
@@ -227,6 +228,7 @@ def snip_quantize_both(x: torch.Tensor, fmt_row: int, fmt_col: int, rule: int = 
     _check(_lib().snip_quantize_both(ptr, rows, cols, ld, rule, ctypes.byref(qr), ctypes.byref(qc),
                                      stats_row.data_ptr() if stats_row is not None else None,
                                      stats_col.data_ptr() if stats_col is not None else None,
+                                     1 if both_formats else 0,
                                      workspace.data_ptr() if workspace is not None else None,
                                      workspace.numel() if workspace is not None else 0, _stream(stream)),
            "snip_quantize_both")

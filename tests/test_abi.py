@@ -71,17 +71,18 @@ def test_quantize_both_validation():
     qr = snip._QTensorC(0x1000, 0x1000, 0, 64, 96, 0)
     qc = snip._QTensorC(0x1000, 0x1000, 0, 96, 64, 1)
     br, bc = ctypes.byref(qr), ctypes.byref(qc)
-    assert L.snip_quantize_both(None, 64, 96, 96, 0, br, bc, None, None, None, 0, None) == 1          # null source
-    assert L.snip_quantize_both(fake, 64, 96, 96, 0, None, bc, None, None, None, 0, None) == 1        # null output
-    assert L.snip_quantize_both(fake, 48, 96, 96, 0, br, bc, None, None, None, 0, None) == 2          # rows % 32
-    assert L.snip_quantize_both(fake, 64, 80, 80, 0, br, bc, None, None, None, 0, None) == 2          # cols % 32
-    assert L.snip_quantize_both(fake, 64, 96, 96, 0, bc, br, None, None, None, 0, None) == 2          # outputs swapped
-    assert L.snip_quantize_both(fake, 64, 96, 96, 0, br, bc, fake, None, fake, 1 << 30, None) == 1    # one statistics output
-    assert L.snip_quantize_both(fake, 64, 96, 96, 0, br, bc, fake, fake, None, 0, None) == 5          # workspace
+    assert L.snip_quantize_both(None, 64, 96, 96, 0, br, bc, None, None, 0, None, 0, None) == 1          # null source
+    assert L.snip_quantize_both(fake, 64, 96, 96, 0, None, bc, None, None, 0, None, 0, None) == 1        # null output
+    assert L.snip_quantize_both(fake, 48, 96, 96, 0, br, bc, None, None, 0, None, 0, None) == 2          # rows % 32
+    assert L.snip_quantize_both(fake, 64, 80, 80, 0, br, bc, None, None, 0, None, 0, None) == 2          # cols % 32
+    assert L.snip_quantize_both(fake, 64, 96, 96, 0, bc, br, None, None, 0, None, 0, None) == 2          # outputs swapped
+    assert L.snip_quantize_both(fake, 64, 96, 96, 0, br, bc, fake, None, 0, fake, 1 << 30, None) == 1    # one statistics output
+    assert L.snip_quantize_both(fake, 64, 96, 96, 0, br, bc, fake, fake, 0, None, 0, None) == 5          # workspace
+    assert L.snip_quantize_both(fake, 64, 96, 96, 0, br, bc, None, None, 7, None, 0, None) == 3           # scope
     bad = snip._QTensorC(0x1000, 0x1000, 0, 96, 64, 5)
-    assert L.snip_quantize_both(fake, 64, 96, 96, 0, br, ctypes.byref(bad), None, None, None, 0, None) == 3   # format
+    assert L.snip_quantize_both(fake, 64, 96, 96, 0, br, ctypes.byref(bad), None, None, 0, None, 0, None) == 3   # format
     odd = snip._QTensorC(0x1008, 0x1000, 0, 96, 64, 1)
-    assert L.snip_quantize_both(fake, 64, 96, 96, 0, br, ctypes.byref(odd), None, None, None, 0, None) == 4   # alignment
+    assert L.snip_quantize_both(fake, 64, 96, 96, 0, br, ctypes.byref(odd), None, None, 0, None, 0, None) == 4   # alignment
 
 
 def test_gemm_norm_validation_and_workspace_size():

@@ -96,6 +96,24 @@ def test_config1_tensors():
         check(snip, bits, oracle.FP8, oracle.FP4, oracle.NO_OVERFLOW, with_stats=True)
 
 
+@pytest.mark.parametrize("fmt_r", FMTS)
+@pytest.mark.parametrize("fmt_c", FMTS)
+@pytest.mark.parametrize("rule", RULES)
+def test_statistics_of_both_formats_from_the_same_pass(fmt_r, fmt_c, rule):
+    """both_formats=True: the complete triple for either direction (what the statistics pass delivers), next to the
+    same codes and scales."""
+    snip = require_gpu()
+    rng = np.random.default_rng(300 + fmt_r + 2 * fmt_c + 4 * rule)
+    bits = wl.f32_to_bf16_bits((rng.standard_t(3, size=(288, 1184)) * 0.3).astype(np.float32))
+    sr, sc = snip.alloc_stats(), snip.alloc_stats()
+    qr, qc = snip.snip_quantize_both(to_dev(bits), fmt_r, fmt_c, rule, stats_row=sr, stats_col=sc, both_formats=True)
+    torch.cuda.synchronize()
+    for q, st, fmt, axis in ((qr, sr, fmt_r, oracle.ROW), (qc, sc, fmt_c, oracle.COL)):
+        want_c, want_s = oracle.quantize(bits, fmt, axis, rule)
+        assert np.array_equal(host(q.scales), want_s) and np.array_equal(host(q.codes), want_c)
+        np.testing.assert_allclose(host(st), oracle.stats(bits, axis, rule), rtol=TOL)
+
+
 def test_equals_single_orientation_calls_and_is_deterministic():
     """Same bytes as the two separate calls (which the other tests tie to the oracle) on a tensor too large for
     the oracle to be run in the test: 2048 x 4224."""

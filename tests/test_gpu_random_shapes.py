@@ -65,6 +65,14 @@ def test_quantize_random_shapes(case):
     check_q(qc, bits, fc, oracle.COL, rule)
     check_stats(sr, bits, fr, oracle.ROW, rule)
     check_stats(sc, bits, fc, oracle.COL, rule)
+    # the same call with the statistics of both formats
+    fr2, fc2 = snip.alloc_stats(), snip.alloc_stats()
+    snip.snip_quantize_both(x, fr, fc, rule, out_row=qr, out_col=qc, stats_row=fr2, stats_col=fc2, both_formats=True)
+    torch.cuda.synchronize()
+    check_q(qr, bits, fr, oracle.ROW, rule)
+    check_q(qc, bits, fc, oracle.COL, rule)
+    np.testing.assert_allclose(host(fr2), oracle.stats(bits, oracle.ROW, rule), rtol=1e-5)
+    np.testing.assert_allclose(host(fc2), oracle.stats(bits, oracle.COL, rule), rtol=1e-5)
     # the single-orientation kernels
     s1, s2 = snip.alloc_stats(), snip.alloc_stats()
     q1 = snip.snip_quantize(x, fc, snip.ROW, rule, stats=s1)
