@@ -107,6 +107,13 @@ def test_linear_at_full_size(config, plan_name, linear):
             k = 2 if f == snip.FP8 else 1
             np.testing.assert_allclose(host(st)[[0, k]], host(ref)[[0, k]], rtol=1e-5)
             assert np.isnan(host(st)[3 - k])
+        # the same call with the statistics of both formats: the complete record of the statistics pass
+        got_r, got_c = snip.snip_quantize_both(t_dev, f_r, f_c, out_row=got_r, out_col=got_c, stats_row=st_r, stats_col=st_c,
+                                               both_formats=True)
+        torch.cuda.synchronize()
+        assert torch.equal(got_r.codes, want_r.codes) and torch.equal(got_c.codes, want_c.codes)
+        np.testing.assert_allclose(host(st_r), host(ref_r), rtol=1e-5)
+        np.testing.assert_allclose(host(st_c), host(ref_c), rtol=1e-5)
         del got_r, got_c
 
     # ---- the one-read statistics of both block directions (what the benchmark step calls) agree with the
