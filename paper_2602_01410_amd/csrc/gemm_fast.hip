@@ -18,11 +18,12 @@
 //   The result tile leaves through LDS as well: each wave transposes its 128 x 64 block so that the
 //   global stores are 16 bytes per lane and 128 contiguous bytes per row.
 //
-// Measured with shader-clock stamps around every phase (FP4 x FP4, 256 contraction elements per
-// stage): an MFMA phase takes 505 cycles (16 MFMAs x 32), a read phase 390 (one wave issues a
-// ds_read_b128 about every 29 cycles whatever the other waves do), a barrier 40-60.  Under load
-// the clock sits near 1.45 GHz on random codes (1.8 GHz on all-zero codes): the kernel is limited by
-// power, so removing idle cycles gains less than proportionally.
+// Measured with s_memtime stamps around every phase (FP4 x FP4, 256 contraction elements per
+// stage): an MFMA phase takes 505 ticks (16 MFMAs x 32), a read phase 390 (one wave issues a
+// ds_read_b128 about every 29 ticks whatever the other waves do), a barrier 40-60.  Under load
+// the ticks arrive at 1.1-1.45 G/s on random codes and 1.8 G/s on all-zero codes (the shader clock shown
+// by the system tools falls from 2.4 to 1.85-1.9 GHz likewise): the kernel is limited by power, so
+// removing idle cycles gains less than proportionally.
 //
 // See gemm.hip for the register layout of v_mfma_scale_f32_32x32x64_f8f6f4.
 #include "snip_internal.h"
