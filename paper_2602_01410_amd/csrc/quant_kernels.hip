@@ -788,8 +788,8 @@ __global__ __launch_bounds__(256) void stats_col_kernel(const uint16_t* __restri
 // Grid and ownership as in stats_col_kernel: a wave owns 128 columns and a range of 32-row blocks; a lane
 // reads two adjacent columns of every row.  The column-direction errors come straight from those registers
 // (a column's block never leaves the lane).  For the row direction the raw 32 x 128 tile goes through the
-// wave's 8 KB of LDS and comes back as eight 16-byte pieces per lane, 8 consecutive elements of one row each,
-// so that four neighbouring lanes hold one 32-element block exactly as in the row kernels.  LDS operations
+// wave's 8 KB of LDS and comes back as eight 16-byte pieces per lane: two whole 32-element row blocks, so that
+// the row direction, too, forms a block's maximum and scales inside one lane.  LDS operations
 // of one wave execute in order, so no barrier is needed between the writes and the reads.
 // partials: [waves][6] = {sum x^2, row err4, row err8, sum x^2, col err4, col err8}.
 template <int RULE>
@@ -808,6 +808,14 @@ __global__ __launch_bounds__(256) void stats_both_kernel(const uint16_t* __restr
     const int rb0 = (int)((int64_t)nrb * split / nsplit), rb1 = (int)((int64_t)nrb * (split + 1) / nsplit);
     float t0 = 0.f, r4 = 0.f, r8 = 0.f, c4 = 0.f, c8 = 0.f;
     bool bad = false;
+    // LDS image of the raw tile: row i holds its sixteen 16-byte pieces at positions piece ^ (i % 4), so that the
+    // 16 lanes served together by a 16-byte read (4 rows x 4 blocks) fall into 16 different bank groups.
+    int wpos[4], rpos[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        wpos[t] = (((lane >> 2) ^ t) << 2) | (lane & 3);                                   // dword lane of a row with i % 4 == t
+        rpos[t] = (lane >> 2) * 64 + ((((lane & 3) * 4 + t) ^ ((lane >> 2) & 3)) << 2);    // piece t of block lane % 4, row lane / 4
+    }
     for (int cg = wave_x; cg < ncg; cg += nwaves_x) {
         const int c = cg * kColsPerWave + lane * 2;
         const bool act = c < cols;
@@ -817,7 +825,7 @@ __global__ __launch_bounds__(256) void stats_both_kernel(const uint16_t* __restr
 #pragma unroll
             for (int i = 0; i < 32; ++i) v[i] = act ? *reinterpret_cast<const unsigned*>(p + (int64_t)i * ld) : 0u;
 #pragma unroll
-            for (int i = 0; i < 32; ++i) raw[i * 64 + lane] = v[i];
+            for (int i = 0; i < 32; ++i) raw[i * 64 + wpos[i & 3]] = v[i];
             // ---- column direction ----
             unsigned m = 0;
 #pragma unroll
@@ -842,20 +850,32 @@ __global__ __launch_bounds__(256) void stats_both_kernel(const uint16_t* __restr
                 }
                 bad |= b8 == 0xFFu;
             }
-            // ---- row direction: piece j of this lane = elements [8 (idx % 16), +8) of tile row idx / 16 ----
+            // ---- row direction: the lane takes two whole blocks, block lane % 4 of tile rows lane / 4 and
+            //      16 + lane / 4, as four 16-byte pieces each, so that a block's maximum and its two scales are
+            //      formed once per 32 elements, inside the lane ----
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int idx = j * 64 + lane;
-                const uint4 q = *reinterpret_cast<const uint4*>(raw + (idx >> 4) * 64 + (idx & 15) * 4);
-                const unsigned am = quad_max(amax8(q));
+            for (int h = 0; h < 2; ++h) {
+                uint4 q[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) q[k] = *reinterpret_cast<const uint4*>(raw + h * 16 * 64 + rpos[k]);
+                unsigned m = 0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    m = pk_max_u16(m, pk_max_u16(pk_max_u16(q[k].x & 0x7FFF7FFFu, q[k].y & 0x7FFF7FFFu),
+                                                 pk_max_u16(q[k].z & 0x7FFF7FFFu, q[k].w & 0x7FFF7FFFu)));
+                const unsigned lo = m & 0xFFFFu, hi = m >> 16;
+                const unsigned am = lo > hi ? lo : hi;
                 const unsigned b8 = scale_byte<kFP8, RULE>(am), b4 = scale_byte<kFP4, RULE>(am);
                 const float sc8 = scale_operand(b8), sc4 = scale_operand(b4);
-                const unsigned ww[4] = {q.x, q.y, q.z, q.w};
-                const unsigned e0 = enc8<RULE>(ww[0], ww[1], sc8, b8), e1 = enc8<RULE>(ww[2], ww[3], sc8, b8);
-                const unsigned e4 = enc4(ww[0], ww[1], ww[2], ww[3], sc4);
                 float dummy = 0.f;
-                err8(ww, e0, e1, sc8, dummy, r8, false);
-                err4(ww, e4, sc4, dummy, r4, false);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const unsigned ww[4] = {q[k].x, q[k].y, q[k].z, q[k].w};
+                    const unsigned e0 = enc8<RULE>(ww[0], ww[1], sc8, b8), e1 = enc8<RULE>(ww[2], ww[3], sc8, b8);
+                    const unsigned e4 = enc4(ww[0], ww[1], ww[2], ww[3], sc4);
+                    err8(ww, e0, e1, sc8, dummy, r8, false);
+                    err4(ww, e4, sc4, dummy, r4, false);
+                }
                 bad |= b8 == 0xFFu;
             }
         }
