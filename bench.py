@@ -48,8 +48,9 @@ def parse():
                    help="one quantize call per orientation (two reads of a tensor wanted in both) instead of snip_quantize_both")
     p.add_argument("--library-reference", action="store_true",
                    help="time the vendor library's GEMMs beside snip_gemm_fwd on the 7B shapes, print JSON and exit")
-    p.add_argument("--microbench", action="store_true",
-                   help="run the device microbenchmarks (measured MFMA / HBM / L2 rates) and exit")
+    p.add_argument("--microbench", nargs="?", const="default", default=None, choices=["default", "hbm-sweep"],
+                   help="run the device microbenchmarks (measured MFMA / HBM / L2 rates; `hbm-sweep`: copy / read / write "
+                        "rates over launch shapes, loads in flight, access widths and non-temporal hints) and exit")
     return p.parse_args()
 
 
@@ -365,7 +366,7 @@ def main():
     if args.microbench:
         import subprocess
         exe = os.path.join(ROOT, "paper_2602_01410_amd", "snip_microbench")
-        sys.exit(subprocess.run([exe]).returncode)
+        sys.exit(subprocess.run([exe] + ([] if args.microbench == "default" else [args.microbench])).returncode)
     from paper_2602_01410_amd import snip, workloads as wl
     if args.library_reference:
         snip._lib()

@@ -335,6 +335,23 @@ snip_status snip_quant_error_stats_both(const void* x, int64_t rows, int64_t col
                                         snip_stats* out_col, void* workspace,
                                         size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): snip_quant_error_stats with its workspace
+ * taken from an array that is part of the library's device image (about 24 MiB, resident on every
+ * GPU the library is used on until the process ends).  Same arguments, results and error behaviour
+ * as snip_quant_error_stats without the workspace pair, except:
+ *   - cols must not exceed snip_noalloc_max_cols() (32768): SNIP_ERR_WORKSPACE otherwise;
+ *   - the device is the current one (hipGetDevice) and `stream` must belong to it;
+ *   - all calls on one GPU share the array: calls that overlap in time on one GPU (different
+ *     streams, different threads) race and must be serialized by the caller.  Nothing in the
+ *     array has to start at zero; every word a call reads it has written itself.
+ * The call allocates nothing and frees nothing; the first call on a device looks up the array's
+ * device address (hipGetSymbolAddress), later calls reuse it. */
+size_t snip_noalloc_max_cols(void);
+snip_status snip_quant_error_stats_noalloc(const void* x, int64_t rows, int64_t cols, int64_t ld,
+                                           snip_axis axis, snip_scale_rule rule,
+                                           snip_stats* out, float* per_line, void* stream);
+
 const char* snip_status_string(snip_status s);
 
 #ifdef __cplusplus

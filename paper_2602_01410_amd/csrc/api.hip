@@ -2,8 +2,16 @@
 #include "../../include/snip.h"
 #include "snip_internal.h"
 #include <cmath>
+#include <mutex>
 
 using namespace snip;
+
+// Scratch of snip_quant_error_stats_noalloc: the workspace of the statistics kernels for a source of up to
+// kNoallocMaxCols columns, resident on every device the library is used on.  In host code this name is only a
+// handle for hipGetSymbolAddress; kernels and launchers get the device address kept in g_scratch_ptr.
+constexpr int64_t kNoallocMaxCols = 32768;
+constexpr size_t kScratchBytes = stream_workspace_bytes(kNoallocMaxCols);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
 
@@ -394,6 +402,37 @@ snip_status snip_quant_error_stats_both(const void* x, int64_t rows, int64_t col
     a.x = (const uint16_t*)x; a.rows = rows; a.cols = cols; a.ld = ld; a.axis = SNIP_AXIS_ROW; a.rule = rule;
     a.stats = (double*)out_row; a.per_line = nullptr; a.workspace = workspace;
     return launch_stats_both(a, (double*)out_col, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
+}
+
+size_t snip_noalloc_max_cols(void) { return (size_t)kNoallocMaxCols; }
+
+snip_status snip_quant_error_stats_noalloc(const void* x, int64_t rows, int64_t cols, int64_t ld, snip_axis axis,
+                                           snip_scale_rule rule, snip_stats* out, float* per_line, void* stream)
+{
+    snip_status st = check_source(x, rows, cols, ld, axis, rule);
+    if (st != SNIP_OK) return st;
+    if (!out) return SNIP_ERR_NULL;
+    if (cols > kNoallocMaxCols) return SNIP_ERR_WORKSPACE;         // the resident scratch array is sized for this many columns
+    // device address of this device's copy of the array, looked up once per device
+    constexpr int kMaxDevices = 64;
+    static void* g_scratch_ptr[kMaxDevices] = {};
+    static std::mutex g_scratch_mutex;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SNIP_ERR_HIP;
+    void* ptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SNIP_ERR_HIP;
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    StatsArgs a;
+    a.x = (const uint16_t*)x; a.rows = rows; a.cols = cols; a.ld = ld; a.axis = axis; a.rule = rule;
+    a.stats = (double*)out; a.per_line = per_line; a.workspace = ptr;
+    return launch_stats(a, (hipStream_t)stream) == hipSuccess ? SNIP_OK : SNIP_ERR_HIP;
 }
 
 const char* snip_status_string(snip_status s)

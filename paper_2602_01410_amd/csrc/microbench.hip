@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdint>
 #include <cstdlib>
+#include <string>
 #define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); exit(2);} } while (0)
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -81,6 +82,46 @@ __global__ __launch_bounds__(512) void k_l2(const uint8_t* __restrict__ src, siz
     out[blockIdx.x * 512 + threadIdx.x] = ((uint32_t*)buf)[threadIdx.x];
 }
 
+// ---- sweep of streaming kernels: what HBM delivers for a copy, a pure read and a pure write as a function of
+//      the launch shape (workgroups per compute unit), the loads a lane keeps in flight, the access width, the
+//      walk (grid-stride, or one contiguous chunk per workgroup) and non-temporal hints ----
+template <typename T, int U, bool NT, bool CHUNK>
+__global__ __launch_bounds__(256) void k_stream(const T* __restrict__ src, T* __restrict__ dst, size_t n, int mode, uint32_t* sink)
+{
+    // mode 0: copy, 1: read only, 2: write only
+    size_t i, stride, end;
+    if (CHUNK) {
+        const size_t per = (n + gridDim.x - 1) / gridDim.x;
+        i = (size_t)blockIdx.x * per + threadIdx.x; stride = 256; end = (size_t)(blockIdx.x + 1) * per; if (end > n) end = n;
+    } else {
+        i = (size_t)blockIdx.x * 256 + threadIdx.x; stride = (size_t)gridDim.x * 256; end = n;
+    }
+    uint32_t acc = 0;
+    T fill; __builtin_memset(&fill, 0x5A, sizeof(T));
+    for (; i + (U - 1) * stride < end; i += U * stride) {
+        T v[U];
+        if (mode != 2) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = NT ? __builtin_nontemporal_load(src + i + u * stride) : src[i + u * stride];
+        }
+        if (mode == 1) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) { const uint32_t* w = (const uint32_t*)&v[u]; for (unsigned k = 0; k < sizeof(T) / 4; ++k) acc ^= w[k]; }
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const T o = mode == 0 ? v[u] : fill;
+                if (NT) __builtin_nontemporal_store(o, dst + i + u * stride); else dst[i + u * stride] = o;
+            }
+        }
+    }
+    for (; i < end; i += stride) {
+        if (mode == 1) { const T t = src[i]; const uint32_t* w = (const uint32_t*)&t; for (unsigned k = 0; k < sizeof(T) / 4; ++k) acc ^= w[k]; }
+        else dst[i] = mode == 0 ? src[i] : fill;
+    }
+    if (mode == 1 && acc == 0x9E3779B9u) sink[0] = acc;
+}
+
 template <class F> float time_ms(F f, int reps)
 {
     hipEvent_t a, b; CK(hipEventCreate(&a)); CK(hipEventCreate(&b));
@@ -92,8 +133,54 @@ template <class F> float time_ms(F f, int reps)
     return ms / reps;
 }
 
-int main()
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+template <typename T, int U, bool NT, bool CHUNK>
+void sweep_one(const char* tag, const void* s, void* d, size_t bytes, uint32_t* sink)
 {
+    for (int wgpc : {1, 2, 4, 8, 16, 32}) {
+        const int grid = wgpc * 256;
+        double best[3];
+        for (int mode = 0; mode < 3; ++mode) {
+            const float ms = time_ms([&] { k_stream<T, U, NT, CHUNK><<<grid, 256>>>((const T*)s, (T*)d, bytes / sizeof(T), mode, sink); }, 3);
+            best[mode] = (mode == 0 ? 2.0 : 1.0) * bytes / ms / 1e9;
+        }
+        printf("{\"kernel\": \"%s\", \"bytes_per_access\": %d, \"in_flight\": %d, \"nontemporal\": %d, \"walk\": \"%s\", \"wg_per_cu\": %d, "
+               "\"copy_tbps\": %.2f, \"read_tbps\": %.2f, \"write_tbps\": %.2f}\n", tag, (int)sizeof(T), U, (int)NT,
+               CHUNK ? "chunk" : "grid-stride", wgpc, best[0], best[1], best[2]);
+        fflush(stdout);
+    }
+}
+
+int hbm_sweep()
+{
+    const size_t bytes = 2048ull << 20;
+    void *s, *d; CK(hipMalloc(&s, bytes)); CK(hipMalloc(&d, bytes)); CK(hipMemset(s, 1, bytes)); CK(hipMemset(d, 2, bytes));
+    uint32_t* sink; CK(hipMalloc((void**)&sink, 64));
+    {
+        hipStream_t st; CK(hipStreamCreate(&st));
+        const float ms = time_ms([&] { CK(hipMemcpyAsync(d, s, bytes, hipMemcpyDeviceToDevice, st)); CK(hipStreamSynchronize(st)); }, 5);
+        printf("{\"kernel\": \"hipMemcpyAsync device-to-device\", \"copy_tbps\": %.2f}\n", 2.0 * bytes / ms / 1e9);
+        const float ms2 = time_ms([&] { CK(hipMemsetAsync(d, 0, bytes, st)); CK(hipStreamSynchronize(st)); }, 5);
+        printf("{\"kernel\": \"hipMemsetAsync\", \"write_tbps\": %.2f}\n", 1.0 * bytes / ms2 / 1e9);
+    }
+    sweep_one<v4u, 4, false, false>("stream", s, d, bytes, sink);
+    sweep_one<v4u, 8, false, false>("stream", s, d, bytes, sink);
+    sweep_one<v4u, 16, false, false>("stream", s, d, bytes, sink);
+    sweep_one<v4u, 4, true, false>("stream", s, d, bytes, sink);
+    sweep_one<v4u, 8, true, false>("stream", s, d, bytes, sink);
+    sweep_one<v4u, 16, true, false>("stream", s, d, bytes, sink);
+    sweep_one<v4u, 8, false, true>("stream", s, d, bytes, sink);
+    sweep_one<v4u, 8, true, true>("stream", s, d, bytes, sink);
+    sweep_one<unsigned, 8, false, false>("stream", s, d, bytes, sink);
+    sweep_one<unsigned, 16, false, false>("stream", s, d, bytes, sink);
+    sweep_one<unsigned, 16, true, false>("stream", s, d, bytes, sink);
+    return 0;
+}
+
+int main(int argc, char** argv)
+{
+    if (argc > 1 && std::string(argv[1]) == "hbm-sweep") return hbm_sweep();
     int* rnd; CK(hipMalloc(&rnd, 16384 * 4));
     static int h[16384]; srand(1); for (int i = 0; i < 16384; ++i) h[i] = rand() ^ (rand() << 16);
     CK(hipMemcpy(rnd, h, sizeof h, hipMemcpyHostToDevice));

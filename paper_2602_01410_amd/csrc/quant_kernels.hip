@@ -963,8 +963,6 @@ __global__ __launch_bounds__(256) void reduce_lines_kernel(const float* __restri
     per_line[i] = (float)a;
 }
 
-constexpr size_t kPartialBytes = (size_t)kStreamWaves * 6 * sizeof(float);      // [waves][3], or [waves][6] for both directions
-
 int col_splits(int64_t rows, int64_t cols, int* gx)
 {
     const int ncg = (int)((cols + kColsPerWave - 1) / kColsPerWave);
@@ -984,7 +982,7 @@ int col_splits(int64_t rows, int64_t cols, int* gx)
 size_t workspace_bytes(int64_t rows, int64_t cols)
 {
     (void)rows;
-    return kPartialBytes + (size_t)kMaxColSplits * (size_t)cols * 3 * sizeof(float);
+    return stream_workspace_bytes(cols);
 }
 
 // Workgroups for `units` equal work units that waves take in turn: as many waves as give every wave the

@@ -18,6 +18,10 @@ constexpr int kStreamBlocks = 2048;
 constexpr int kWavesPerBlock = 4;
 constexpr int kStreamWaves = kStreamBlocks * kWavesPerBlock;
 constexpr int kMaxColSplits = 64;    // row splits of the column-statistics kernel
+// Workspace of the streaming kernels: [kStreamWaves][6] fp32 wave partials ([..][3] for one block direction),
+// then [kMaxColSplits][cols][3] fp32 per-column partials for the per-line column statistics.
+constexpr size_t kPartialBytes = (size_t)kStreamWaves * 6 * sizeof(float);
+constexpr size_t stream_workspace_bytes(int64_t cols) { return kPartialBytes + (size_t)kMaxColSplits * (size_t)cols * 3 * sizeof(float); }
 constexpr int kG4Align = 256;    // row pitch (in dwords) of the grouped scale copy is a multiple of this
 __host__ __device__ inline int64_t g4_pitch(int64_t rows) { return (rows + kG4Align - 1) / kG4Align * kG4Align; }
 

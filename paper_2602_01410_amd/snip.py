@@ -28,7 +28,8 @@ EXPORTS = ("snip_qtensor_code_bytes", "snip_qtensor_scale_bytes", "snip_qtensor_
            "snip_gemm_workspace_bytes", "snip_gemm_fwd_norm", "snip_gemm_dgrad_norm", "snip_gemm_wgrad_norm",
            "snip_loss_divergence", "snip_quantize_sr_fp4", "snip_quantize_both", "snip_adamw_sensitivity", "snip_weight_divergence",
            "snip_paper_scale_bytes", "snip_paper_workspace_bytes", "snip_quantize_paper",
-           "snip_quant_error_stats_paper", "snip_gemm_paper", "snip_quant_error_stats_both")
+           "snip_quant_error_stats_paper", "snip_gemm_paper", "snip_quant_error_stats_both",
+           "snip_noalloc_max_cols", "snip_quant_error_stats_noalloc")
 
 
 class _PTensorC(ctypes.Structure):
@@ -113,6 +114,10 @@ def _lib():
         lib.snip_quant_error_stats.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, vp, sz, vp]
         lib.snip_quant_error_stats_both.restype = ci
         lib.snip_quant_error_stats_both.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, sz, vp]
+        lib.snip_noalloc_max_cols.restype = sz
+        lib.snip_noalloc_max_cols.argtypes = []
+        lib.snip_quant_error_stats_noalloc.restype = ci
+        lib.snip_quant_error_stats_noalloc.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, vp]
         lib.snip_status_string.restype = ctypes.c_char_p
         lib.snip_status_string.argtypes = [ci]
         _handle = lib
@@ -419,4 +424,15 @@ def snip_quant_error_stats(x: torch.Tensor, axis: int = ROW, rule: int = NO_OVER
                                          per_line.data_ptr() if per_line is not None else None,
                                          workspace.data_ptr(), workspace.numel(), _stream(stream)),
            "snip_quant_error_stats")
+    return out
+
+
+def snip_quant_error_stats_noalloc(x: torch.Tensor, axis: int, rule: int, out: torch.Tensor,
+                                   per_line: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """snip_quant_error_stats on the library's resident scratch array: the binding allocates nothing either, so
+    `out` (and `per_line`, if wanted) must be passed in."""
+    ptr, rows, cols, ld = _src(x)
+    _check(_lib().snip_quant_error_stats_noalloc(ptr, rows, cols, ld, axis, rule, out.data_ptr(),
+                                                 per_line.data_ptr() if per_line is not None else None,
+                                                 _stream(stream)), "snip_quant_error_stats_noalloc")
     return out
