@@ -17,6 +17,11 @@
 //   of the copy so that the 16 lanes served together by a ds_read_b128 hit 16 different bank groups.
 //   The result tile leaves through LDS as well: each wave transposes its 128 x 64 block so that the
 //   global stores are 16 bytes per lane and 128 contiguous bytes per row.
+//   The kernel is persistent: one workgroup per compute unit walks its tiles (dispatch ids blockIdx.x,
+//   blockIdx.x + gridDim.x, ...) and treats their pipeline stages as one sequence, so the first stage of the
+//   next tile is copied into the free stage buffer during the last stage of the current one and a tile's
+//   start-up latency is paid once per workgroup, not once per tile.  The result tile is staged in the other
+//   stage buffer (the one the last stage was read from), 64 KB at a time.
 //
 // Measured with s_memtime stamps around every phase (FP4 x FP4, 256 contraction elements per
 // stage): an MFMA phase takes 505 ticks (16 MFMAs x 32), a read phase 390 (one wave issues a
@@ -36,14 +41,12 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 constexpr int TM = 256, TN = 256;       // workgroup tile
-#ifndef SNIP_WAVES
-#define SNIP_WAVES 8
-#endif
-constexpr int NWAVE = SNIP_WAVES, NT = NWAVE * 64;
-constexpr int WTM = 128, WTN = NWAVE == 8 ? 64 : 128;      // wave tile
-constexpr int WGN = TN / WTN;                              // waves along the B rows (4 or 2)
+constexpr int NWAVE = 8, NT = NWAVE * 64;
+constexpr int WTM = 128, WTN = 64;      // wave tile
+constexpr int WGN = TN / WTN;           // waves along the B rows
 constexpr int MB = WTM / 32, NB = WTN / 32;
 
 // Global -> LDS copy issued by the load unit: lane i's 16 (or 4) bytes land at lds + 16*i (4*i); `lds` is
@@ -78,13 +81,19 @@ template <int FA, int FB> struct FCfg {
     static constexpr int A_BYTES = TM * SBA, B_BYTES = TN * SBB;
     static constexpr int S_BYTES = (TM + TN) * NG * 4;           // scale dwords of one stage
     static constexpr int SLOT = A_BYTES + B_BYTES + S_BYTES;
-    static constexpr int LDS_BYTES = NST * SLOT > 128 * 1024 ? NST * SLOT : 128 * 1024;   // the epilogue stages 128 KB
+    // Stage buffer 0 sits at the start of the LDS array and stage buffer 1 at its end; the result staging area is
+    // the first or the last EPI_BYTES of the array, i.e. it covers the buffer of the tile's last stage (plus the
+    // unused middle) and never reaches into the other buffer, which already receives the next tile.
+    static constexpr int LDS_BYTES = 159 * 1024;
+    static constexpr int SLOT1 = LDS_BYTES - SLOT;
+    static constexpr int EPI_BYTES = 64 * 1024;
     static constexpr int LA = A_BYTES / 1024 / NWAVE;            // 16-byte copy instructions per wave per stage
     static constexpr int LB = B_BYTES / 1024 / NWAVE;
     static constexpr int LS = S_BYTES / 256 / NWAVE;             // 4-byte copy instructions per wave per stage
     static constexpr int L = LA + LB + LS;
-    static_assert(LDS_BYTES >= NWAVE * (128 * 1024 / NWAVE), "the epilogue needs 128 KB of LDS");
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(SLOT1 % 1024 == 0 && SLOT <= SLOT1, "stage buffers must not overlap");
+    static_assert(EPI_BYTES <= LDS_BYTES - SLOT, "the result staging area must stay clear of the other stage buffer");
+    static_assert(LDS_BYTES + 64 <= 160 * 1024, "LDS budget");
 };
 
 // Swizzle: chunk position p of `row` holds logical chunk p ^ f(row); f makes the 16/CPR rows that share
@@ -125,6 +134,30 @@ __device__ __forceinline__ v8i read_frag(const uint8_t* tile, int rowblock_off, 
     return f;
 }
 
+#ifdef SNIP_EXP_STAMP
+__device__ unsigned long long snip_dbg_stamps[64 * 8 * 16];      // [block < 64][wave][slot]
+#define SNIP_STAMP(slot) do { const int sl_ = (slot); if (blockIdx.x < 64 && lane == 0 && sl_ < 16) snip_dbg_stamps[(blockIdx.x * 8 + wave) * 16 + sl_] = wall_clock64(); } while (0)
+#else
+#define SNIP_STAMP(slot) do { } while (0)
+#endif
+
+// Dispatch id -> tile.  Workgroups are dealt round-robin to the 8 XCDs, so ids u, u + 8, u + 16, ... share an L2:
+// each XCD gets a contiguous run of the tile sequence, and the sequence walks bands of 4 tile rows column by
+// column, so that the 32 tiles an XCD works on at a time are a 4 x 8 patch (4 + 8 operand slabs for 32 tiles).
+__device__ __forceinline__ void tile_of(int u, int nblk, int tiles_i, int tiles_j, int& ti, int& tj)
+{
+    int bid = u;
+    const int per = nblk / 8;
+    if (bid < per * 8) bid = (bid % 8) * per + bid / 8;
+    const int band = 4;
+    const int band_sz = band * tiles_j;
+    const int b0 = bid / band_sz;
+    const int rem = bid - b0 * band_sz;
+    const int rows_in_band = min(band, tiles_i - b0 * band);
+    ti = b0 * band + rem % rows_in_band;
+    tj = rem / rows_in_band;
+}
+
 template <int FA, int FB, bool OUT_F32>
 __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict__ a_codes,
                                                        const uint8_t* __restrict__ a_g4,
@@ -135,24 +168,9 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
 {
     using C = FCfg<FA, FB>;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[C::LDS_BYTES];
-    // slot layout: [A codes][B codes][A scale dwords: group-major, 256 rows][B scale dwords]
+    // stage buffer layout: [A codes][B codes][A scale dwords: group-major, 256 rows][B scale dwords]
 
-    // tile order: XCD-contiguous runs, then bands of 4 tile rows walked column by column
     const int nblk = tiles_i * tiles_j;
-    int bid = blockIdx.x;
-    {
-        const int per = nblk / 8;
-        if (bid < per * 8) bid = (bid % 8) * per + bid / 8;
-    }
-    const int band = 4;
-    const int band_sz = band * tiles_j;
-    const int b0 = bid / band_sz;
-    const int rem = bid - b0 * band_sz;
-    const int rows_in_band = min(band, tiles_i - b0 * band);
-    const int ti = b0 * band + rem % rows_in_band;
-    const int tj = rem / rows_in_band;
-    const int i0 = ti * TM, j0 = tj * TN;
-
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
@@ -160,60 +178,67 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
 
     const int64_t a_row_bytes = FA == kFP8 ? R : R / 2;
     const int64_t b_row_bytes = FB == kFP8 ? R : R / 2;
-    const int nstage = R / C::KE;
+    const int nstage = R / C::KE;                                     // >= 2 (gemm_fast_eligible)
     const int64_t a_pitch = g4_pitch(I), b_pitch = g4_pitch(J);      // dwords per scale group
 
-    // ---- source addresses of the global->LDS copies: wave-uniform base + per-lane 32-bit offset ----
-    // Rows past the end of an operand re-read its last row (their products are never stored).
-    unsigned oa[C::LA], ob[C::LB], os[C::LS];
-#pragma unroll
-    for (int j = 0; j < C::LA; ++j) {
-        constexpr int CPR = C::SBA / 16, RPI = 1024 / C::SBA;
-        const int row = (wave * C::LA + j) * RPI + lane / CPR;
-        const int c = (lane % CPR) ^ swz<C::SBA>(row);
-        oa[j] = (unsigned)(min(row, I - 1 - i0) * a_row_bytes + c * 16);
-    }
-#pragma unroll
-    for (int j = 0; j < C::LB; ++j) {
-        constexpr int CPR = C::SBB / 16, RPI = 1024 / C::SBB;
-        const int row = (wave * C::LB + j) * RPI + lane / CPR;
-        const int c = (lane % CPR) ^ swz<C::SBB>(row);
-        ob[j] = (unsigned)(min(row, J - 1 - j0) * b_row_bytes + c * 16);
-    }
-    // scale copy q of a stage: operand, scale group inside the stage, quarter of the 256 tile rows (the
-    // padded pitch of the grouped copy covers whole tiles)
+    // ---- source addresses of the global->LDS copies of ONE tile (the tile the wave's copies currently belong
+    //      to, which runs ahead of the tile being multiplied): wave-uniform base + per-lane 32-bit offset.
+    //      Rows past the end of an operand re-read its last row (their products are never stored). ----
+    unsigned oa[C::LA], ob[C::LB];
+    const unsigned os = lane * 4;
     const uint8_t* sbase[C::LS];
     int64_t sstep[C::LS];
+    const uint8_t* abase;
+    const uint8_t* bbase;
+    auto set_copy_tile = [&](int u) {
+        int ti, tj;
+        tile_of(u, nblk, tiles_i, tiles_j, ti, tj);
+        const int i0 = ti * TM, j0 = tj * TN;
 #pragma unroll
-    for (int j = 0; j < C::LS; ++j) {
-        const int q = wave * C::LS + j;
-        const int opnd = q / (4 * C::NG), grp = (q % (4 * C::NG)) / 4, quarter = q % 4;
-        const int64_t pitch = opnd == 0 ? a_pitch : b_pitch;
-        sbase[j] = (opnd == 0 ? a_g4 : b_g4) + ((int64_t)grp * pitch + (opnd == 0 ? i0 : j0) + quarter * 64) * 4;
-        sstep[j] = (int64_t)C::NG * pitch * 4;
-        os[j] = lane * 4;
-    }
-    const uint8_t* const abase = a_codes + (int64_t)i0 * a_row_bytes;
-    const uint8_t* const bbase = b_codes + (int64_t)j0 * b_row_bytes;
+        for (int j = 0; j < C::LA; ++j) {
+            constexpr int CPR = C::SBA / 16, RPI = 1024 / C::SBA;
+            const int row = (wave * C::LA + j) * RPI + lane / CPR;
+            const int c = (lane % CPR) ^ swz<C::SBA>(row);
+            oa[j] = (unsigned)(min(row, I - 1 - i0) * a_row_bytes + c * 16);
+        }
+#pragma unroll
+        for (int j = 0; j < C::LB; ++j) {
+            constexpr int CPR = C::SBB / 16, RPI = 1024 / C::SBB;
+            const int row = (wave * C::LB + j) * RPI + lane / CPR;
+            const int c = (lane % CPR) ^ swz<C::SBB>(row);
+            ob[j] = (unsigned)(min(row, J - 1 - j0) * b_row_bytes + c * 16);
+        }
+        // scale copy q of a stage: operand, scale group inside the stage, quarter of the 256 tile rows (the
+        // padded pitch of the grouped copy covers whole tiles)
+#pragma unroll
+        for (int j = 0; j < C::LS; ++j) {
+            const int q = wave * C::LS + j;
+            const int opnd = q / (4 * C::NG), grp = (q % (4 * C::NG)) / 4, quarter = q % 4;
+            const int64_t pitch = opnd == 0 ? a_pitch : b_pitch;
+            sbase[j] = (opnd == 0 ? a_g4 : b_g4) + ((int64_t)grp * pitch + (opnd == 0 ? i0 : j0) + quarter * 64) * 4;
+            sstep[j] = (int64_t)C::NG * pitch * 4;
+        }
+        abase = a_codes + (int64_t)i0 * a_row_bytes;
+        bbase = b_codes + (int64_t)j0 * b_row_bytes;
+    };
     const unsigned lds0 = lds_addr(lds);
 
+    // all of this wave's copies of `stage` (of the copy tile) into stage buffer `slot`
     auto issue = [&](int stage, int slot) {
-        const int st = stage;
-        const unsigned base = lds0 + slot * C::SLOT;
+        const unsigned base = lds0 + slot * C::SLOT1;
 #pragma unroll
-        for (int j = 0; j < C::LA; ++j) glds16(abase + (int64_t)st * C::SBA, oa[j], base + (wave * C::LA + j) * 1024);
+        for (int j = 0; j < C::LA; ++j) glds16(abase + (int64_t)stage * C::SBA, oa[j], base + (wave * C::LA + j) * 1024);
 #pragma unroll
-        for (int j = 0; j < C::LB; ++j) glds16(bbase + (int64_t)st * C::SBB, ob[j], base + C::A_BYTES + (wave * C::LB + j) * 1024);
+        for (int j = 0; j < C::LB; ++j) glds16(bbase + (int64_t)stage * C::SBB, ob[j], base + C::A_BYTES + (wave * C::LB + j) * 1024);
 #pragma unroll
-        for (int j = 0; j < C::LS; ++j) glds4(sbase[j] + st * sstep[j], os[j], base + C::A_BYTES + C::B_BYTES + (wave * C::LS + j) * 256);
+        for (int j = 0; j < C::LS; ++j) glds4(sbase[j] + stage * sstep[j], os, base + C::A_BYTES + C::B_BYTES + (wave * C::LS + j) * 256);
     };
-
     // copy instruction j (0 .. L-1) of this wave's share of a stage
     auto issue_one = [&](int j, int stage, int slot) {
-        const unsigned base = lds0 + slot * C::SLOT;
+        const unsigned base = lds0 + slot * C::SLOT1;
         if (j < C::LA) glds16(abase + (int64_t)stage * C::SBA, oa[j], base + (wave * C::LA + j) * 1024);
         else if (j < C::LA + C::LB) { const int k = j - C::LA; glds16(bbase + (int64_t)stage * C::SBB, ob[k], base + C::A_BYTES + (wave * C::LB + k) * 1024); }
-        else { const int k = j - C::LA - C::LB; glds4(sbase[k] + stage * sstep[k], os[k], base + C::A_BYTES + C::B_BYTES + (wave * C::LS + k) * 256); }
+        else { const int k = j - C::LA - C::LB; glds4(sbase[k] + stage * sstep[k], os, base + C::A_BYTES + C::B_BYTES + (wave * C::LS + k) * 256); }
     };
 
     // ---- per-lane LDS read offsets ----
@@ -225,12 +250,6 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
     const int scb_off = C::A_BYTES + C::B_BYTES + TM * C::NG * 4 + (wn * WTN + r32) * 4;
 
     v16f acc[MB][NB];
-#pragma unroll
-    for (int a = 0; a < MB; ++a)
-#pragma unroll
-        for (int b = 0; b < NB; ++b)
-#pragma unroll
-            for (int k = 0; k < 16; ++k) acc[a][b][k] = 0.f;
 
     // ---- ping-pong schedule.  The two waves that share a SIMD (wave w and w + 4) belong to different
     //      groups.  A stage is two phases; in every phase a wave either reads its operands of that phase
@@ -240,161 +259,136 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
     //          barrier    b0      b1      b2      b3      b4      b5 ...
     //          group 0        R0(0)   M0(0)   R1(0)   M1(0)   R0(1)   M0(1)
     //          group 1        -       R0(0)   M0(0)   R1(0)   M1(0)   R0(1)
-    //      Stage s is complete in LDS before b(4s): every wave waits for its own copies before that barrier.
-    //      The slot of stage s is free after b(4s+4): group 1, the last reader, waits for its R1(s) data
-    //      before that barrier, so no read of the slot is in flight when the first copy into it is issued. ----
-    {
-        constexpr int KP = C::KS / 2;                      // k-steps per phase
-        v8i fa[KP][MB], fb[KP][NB];
-        unsigned sa[MB], sb[NB];
-        auto R = [&](int slot, int p) {
-            const uint8_t* base = lds + slot * C::SLOT;
-            const uint8_t* ta = base + wm * WTM * C::SBA;
-            const uint8_t* tb = base + C::A_BYTES + wn * WTN * C::SBB;
-            const int q = C::NG == 2 ? p : 0;
+    //      Stage s of a tile is complete in LDS before b(4s): every wave waits for its own copies before that
+    //      barrier.  The buffer of stage s is free after b(4s+4): group 1, the last reader, waits for its R1(s)
+    //      data before that barrier, so no read of the buffer is in flight when the first copy into it is issued.
+    //      Stages alternate between the two buffers across tiles as well: stage s of a tile uses buffer
+    //      (s + par) & 1, par being the number of stages of all earlier tiles mod 2.
+    //      At the end of a tile (S stages): group 0 has issued its share of the next tile's stage 0 during
+    //      M0(S-1) and group 1 during M1(S-2), both into the buffer that stage S would use.  After b(4S) group 0
+    //      stores its result block through the staging area (which covers the last stage's buffer, free since
+    //      b(4S)) while group 1 still issues M1(S-1), then group 1 stores its block; the next tile's b(0) follows.
+    //      Group 1's share of the next tile's stage 1, which goes into the buffer under the staging area, is
+    //      issued after that barrier (where the first tile issues it, too). ----
+    constexpr int KP = C::KS / 2;                      // k-steps per phase
+    v8i fa[KP][MB], fb[KP][NB];
+    unsigned sa[MB], sb[NB];
+    auto RD = [&](int slot, int p) {
+        const uint8_t* base = lds + slot * C::SLOT1;
+        const uint8_t* ta = base + wm * WTM * C::SBA;
+        const uint8_t* tb = base + C::A_BYTES + wn * WTN * C::SBB;
+        const int q = C::NG == 2 ? p : 0;
 #pragma unroll
-            for (int m = 0; m < MB; ++m) sa[m] = *reinterpret_cast<const unsigned*>(base + sca_off + q * TM * 4 + m * 128) >> (8 * g);
+        for (int m = 0; m < MB; ++m) sa[m] = *reinterpret_cast<const unsigned*>(base + sca_off + q * TM * 4 + m * 128) >> (8 * g);
 #pragma unroll
-            for (int n = 0; n < NB; ++n) sb[n] = *reinterpret_cast<const unsigned*>(base + scb_off + q * TN * 4 + n * 128) >> (8 * g);
+        for (int n = 0; n < NB; ++n) sb[n] = *reinterpret_cast<const unsigned*>(base + scb_off + q * TN * 4 + n * 128) >> (8 * g);
 #pragma unroll
-            for (int k = 0; k < KP; ++k) {
+        for (int k = 0; k < KP; ++k) {
 #pragma unroll
-                for (int m = 0; m < MB; ++m) fa[k][m] = read_frag<FA>(ta, m * 32 * C::SBA, offa, p * KP + k);
+            for (int m = 0; m < MB; ++m) fa[k][m] = read_frag<FA>(ta, m * 32 * C::SBA, offa, p * KP + k);
 #pragma unroll
-                for (int n = 0; n < NB; ++n) fb[k][n] = read_frag<FB>(tb, n * 32 * C::SBB, offb, p * KP + k);
-            }
-        };
-        // The MFMAs of phase p.  With COPY the wave's L copy instructions of stage `nxt` into `nslot` are
-        // spread evenly between the phase's NM MFMAs (the sched_barriers keep them there).
-        constexpr int NM = KP * MB * NB;
-        auto M = [&](auto copy_tag, int p, int nxt, int nslot) {
-            constexpr bool COPY = decltype(copy_tag)::value;
-            constexpr int ca = FB == kFP8 ? 0 : 4, cb = FA == kFP8 ? 0 : 4;
-            __builtin_amdgcn_s_setprio(1);
-            int idx = 0;
-#pragma unroll
-            for (int k = 0; k < KP; ++k) {
-                const int ks = p * KP + k;
-#pragma unroll
-                for (int m = 0; m < MB; ++m)
-#pragma unroll
-                    for (int n = 0; n < NB; ++n) {
-                        if ((ks & 1) == 0)
-                            acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[k][n], fa[k][m], acc[m][n], ca, cb, 0, (int)sb[n], 0, (int)sa[m]);
-                        else
-                            acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[k][n], fa[k][m], acc[m][n], ca, cb, 2, (int)sb[n], 2, (int)sa[m]);
-                        if (COPY) {
-                            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                            for (int j = 0; j < C::L; ++j)
-                                if (j * NM / C::L == idx) issue_one(j, nxt, nslot);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                        ++idx;
-                    }
-            }
-            __builtin_amdgcn_s_setprio(0);
-        };
-        const std::true_type with_copy{};
-        const std::false_type no_copy{};
-#define SNIP_BAR() do { __builtin_amdgcn_sched_barrier(0); __builtin_amdgcn_s_barrier(); __builtin_amdgcn_sched_barrier(0); } while (0)
-        issue(0, 0);
-        if (wave < NWAVE / 2) {
-            // group 0 issues its copies of stage s+1 during M0(s), between b(4s+1) and b(4s+2)
-            auto stage0 = [&](auto copy_tag, int s) {
-                const int slot = s & 1;
-                SNIP_WAIT_VM(0); SNIP_BAR();                       // b(4s)
-                R(slot, 0); SNIP_BAR();                            // b(4s+1)
-                M(copy_tag, 0, s + 1, slot ^ 1); SNIP_BAR();       // b(4s+2)
-                R(slot, 1); SNIP_BAR();                            // b(4s+3)
-                M(no_copy, 1, 0, 0);
-            };
-            for (int s = 0; s < nstage - 1; ++s) stage0(with_copy, s);
-            stage0(no_copy, nstage - 1);
-            SNIP_BAR();                                            // b(4S)
-        } else {
-            // group 1 issues its copies of stage s+2 during M1(s), between b(4s+4) and b(4s+5); those of
-            // stage 1 while it idles through the first phase
-            auto stage1 = [&](auto copy_tag, int s) {
-                const int slot = s & 1;
-                SNIP_BAR();                                        // b(4s+1)
-                R(slot, 0); SNIP_BAR();                            // b(4s+2)
-                M(no_copy, 0, 0, 0); SNIP_BAR();                   // b(4s+3)
-                R(slot, 1);
-                __builtin_amdgcn_s_waitcnt(0x0070);                // vmcnt(0) and lgkmcnt(0)
-                SNIP_BAR();                                        // b(4s+4)
-                M(copy_tag, 1, s + 2, slot);
-            };
-            SNIP_WAIT_VM(0); SNIP_BAR();                           // b(0)
-            if (nstage > 1) issue(1, 1);
-            for (int s = 0; s < nstage - 2; ++s) stage1(with_copy, s);
-            if (nstage > 1) stage1(no_copy, nstage - 2);
-            stage1(no_copy, nstage - 1);
+            for (int n = 0; n < NB; ++n) fb[k][n] = read_frag<FB>(tb, n * 32 * C::SBB, offb, p * KP + k);
         }
-#undef SNIP_BAR
-    }
-    SNIP_WAIT_VM(0);            // no copy may still be in flight when the LDS is reused below or handed to another workgroup
-    __builtin_amdgcn_s_barrier();
-
-    // ---- optional: sum of squares of the tile as it will be stored (rounded to the output type), elements
-    //      outside the matrix excluded; one partial per workgroup, combined by a second kernel.  Interior
-    //      tiles take the short path: bf16 pairs are squared and added by v_dot2c_f32_bf16. ----
-    if (norm_partials) {
-        __shared__ float wave_ss[NWAVE];
-        float ss = 0.f;
-        if (i0 + TM <= I && j0 + TN <= J) {
+    };
+    // The MFMAs of phase p.  With COPY the wave's L copy instructions of stage `nxt` (of the copy tile) into
+    // buffer `nslot` are spread evenly between the phase's NM MFMAs (the sched_barriers keep them there).
+    constexpr int NM = KP * MB * NB;
+    auto MM = [&](auto copy_tag, int p, int nxt, int nslot) {
+        constexpr bool COPY = decltype(copy_tag)::value;
+        constexpr int ca = FB == kFP8 ? 0 : 4, cb = FA == kFP8 ? 0 : 4;
+        __builtin_amdgcn_s_setprio(1);
+        int idx = 0;
+#pragma unroll
+        for (int k = 0; k < KP; ++k) {
+            const int ks = p * KP + k;
 #pragma unroll
             for (int m = 0; m < MB; ++m)
 #pragma unroll
-                for (int n = 0; n < NB; ++n)
+                for (int n = 0; n < NB; ++n) {
+                    if ((ks & 1) == 0)
+                        acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[k][n], fa[k][m], acc[m][n], ca, cb, 0, (int)sb[n], 0, (int)sa[m]);
+                    else
+                        acc[m][n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[k][n], fa[k][m], acc[m][n], ca, cb, 2, (int)sb[n], 2, (int)sa[m]);
+                    if (COPY) {
+                        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int k = 0; k < 16; k += 2) {
-                        if (OUT_F32) {
-                            ss = fmaf(acc[m][n][k], acc[m][n][k], ss);
-                            ss = fmaf(acc[m][n][k + 1], acc[m][n][k + 1], ss);
-                        } else {
-                            const float2_t pr = {acc[m][n][k], acc[m][n][k + 1]};
-                            const bf16x2 r = __builtin_convertvector(pr, bf16x2);
-                            const unsigned rb = __builtin_bit_cast(unsigned, r);
-                            asm("v_dot2c_f32_bf16 %0, %1, %1" : "+v"(ss) : "v"(rb));       // ss += r.x * r.x + r.y * r.y
+                        for (int j = 0; j < C::L; ++j)
+                            if (j * NM / C::L == idx) issue_one(j, nxt, nslot);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    ++idx;
+                }
+        }
+        __builtin_amdgcn_s_setprio(0);
+    };
+    const std::true_type with_copy{};
+    const std::false_type no_copy{};
+#define SNIP_BAR() do { __builtin_amdgcn_sched_barrier(0); __builtin_amdgcn_s_barrier(); __builtin_amdgcn_sched_barrier(0); } while (0)
+
+    // ---- result of tile u: optional sum of squares, then every wave transposes its 128 x 64 block through its
+    //      own 8 KB of the staging area at byte `ebase` of the LDS array ----
+    auto store_tile = [&](int u, int ebase) {
+        int ti, tj;
+        tile_of(u, nblk, tiles_i, tiles_j, ti, tj);
+        const int i0 = ti * TM, j0 = tj * TN;
+        const bool interior = i0 + TM <= I && j0 + TN <= J;
+        // optional: sum of squares of the tile as it will be stored (rounded to the output type), elements
+        // outside the matrix excluded; one partial per tile, combined by a second kernel.  Interior tiles take
+        // the short path: bf16 pairs are squared and added by v_dot2c_f32_bf16.
+        if (norm_partials) {
+            __shared__ float wave_ss[NWAVE];
+            float ss = 0.f;
+            if (interior) {
+#pragma unroll
+                for (int m = 0; m < MB; ++m)
+#pragma unroll
+                    for (int n = 0; n < NB; ++n)
+#pragma unroll
+                        for (int k = 0; k < 16; k += 2) {
+                            if (OUT_F32) {
+                                ss = fmaf(acc[m][n][k], acc[m][n][k], ss);
+                                ss = fmaf(acc[m][n][k + 1], acc[m][n][k + 1], ss);
+                            } else {
+                                const float2_t pr = {acc[m][n][k], acc[m][n][k + 1]};
+                                const bf16x2 r = __builtin_convertvector(pr, bf16x2);
+                                const unsigned rb = __builtin_bit_cast(unsigned, r);
+                                asm("v_dot2c_f32_bf16 %0, %1, %1" : "+v"(ss) : "v"(rb));       // ss += r.x * r.x + r.y * r.y
+                            }
                         }
-                    }
-        } else {
+            } else {
 #pragma unroll
-            for (int m = 0; m < MB; ++m) {
-                const bool row_ok = i0 + wm * WTM + m * 32 + r32 < I;
+                for (int m = 0; m < MB; ++m) {
+                    const bool row_ok = i0 + wm * WTM + m * 32 + r32 < I;
 #pragma unroll
-                for (int n = 0; n < NB; ++n)
+                    for (int n = 0; n < NB; ++n)
 #pragma unroll
-                    for (int k = 0; k < 16; ++k) {
-                        const int col = j0 + wn * WTN + n * 32 + 8 * (k >> 2) + 4 * g + (k & 3);
-                        float v = acc[m][n][k];
-                        if (!OUT_F32) v = (float)(__bf16)v;
-                        ss = (row_ok && col < J) ? fmaf(v, v, ss) : ss;
-                    }
+                        for (int k = 0; k < 16; ++k) {
+                            const int col = j0 + wn * WTN + n * 32 + 8 * (k >> 2) + 4 * g + (k & 3);
+                            float v = acc[m][n][k];
+                            if (!OUT_F32) v = (float)(__bf16)v;
+                            ss = (row_ok && col < J) ? fmaf(v, v, ss) : ss;
+                        }
+                }
+            }
+            for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+            if (lane == 0) wave_ss[wave] = ss;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                float t = 0.f;
+                for (int w = 0; w < NWAVE; ++w) t += wave_ss[w];
+                norm_partials[u] = t;
             }
         }
-        for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
-        if (lane == 0) wave_ss[wave] = ss;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            float t = 0.f;
-            for (int w = 0; w < NWAVE; ++w) t += wave_ss[w];
-            norm_partials[blockIdx.x] = t;
-        }
-    }
-
-    // ---- epilogue: every wave transposes its 128 x 64 block through its own 16 KB of LDS ----
-    // In registers, lane (r32, g) of block (m, n) holds C[32m + r32][32n + 8q + 4g + t] in acc[m][n][4q + t].
-    // In LDS a row is ROWB bytes of 16-byte chunks, chunk c of row r stored at position c ^ f(r).
-    {
+        // In registers, lane (r32, g) of block (m, n) holds C[32m + r32][32n + 8q + 4g + t] in acc[m][n][4q + t].
+        // In LDS a row is ROWB bytes of 16-byte chunks, chunk c of row r stored at position c ^ f(r).
         constexpr int ESZ = OUT_F32 ? 4 : 2;
         constexpr int ROWB = WTN * ESZ;                  // 128 or 256 bytes per row
         constexpr int CPR = ROWB / 16;                   // 8 or 16 chunks per row
-        constexpr int REGION = 128 * 1024 / NWAVE;       // LDS bytes a wave may use
+        constexpr int REGION = C::EPI_BYTES / NWAVE;     // LDS bytes a wave may use
         constexpr int ROWS_PER_PASS = REGION / ROWB < WTM ? REGION / ROWB : WTM;
         constexpr int MB_PER_PASS = ROWS_PER_PASS / 32;
-        uint8_t* reg = lds + wave * REGION;
+        static_assert(MB_PER_PASS >= 1 && MB % MB_PER_PASS == 0, "staging passes must be whole 32-row blocks");
+        uint8_t* reg = lds + ebase + wave * REGION;
 #pragma unroll
         for (int pass = 0; pass < MB / MB_PER_PASS; ++pass) {
 #pragma unroll
@@ -420,40 +414,153 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                         }
                     }
             }
-            // read back row-contiguous: 64 lanes cover 64 / CPR rows per instruction
+            // read back row-contiguous: 64 lanes cover 64 / CPR rows per instruction.  Streaming stores: all
+            // workgroups finish a tile at about the same time (32 MB per round of tiles, the size of all L2s
+            // together); lines that nobody here reads again should not push the operands out of the caches.
             constexpr int RPI = 64 / CPR;
+            if (interior) {
+                // whole tile inside the matrix (wave-uniform): no per-lane tests, one wave-uniform base per
+                // instruction plus a 32-bit lane offset
+                const unsigned lane_off = (unsigned)((lane / CPR) * (int)ldc * ESZ + (lane % CPR) * 16);
+                const uint8_t* cb = reinterpret_cast<const uint8_t*>(c_out) +
+                                    ((int64_t)(i0 + wm * WTM + pass * ROWS_PER_PASS) * ldc + j0 + wn * WTN) * ESZ;
 #pragma unroll
-            for (int it = 0; it < ROWS_PER_PASS / RPI; ++it) {
-                const int row = it * RPI + lane / CPR;
-                const int c = lane % CPR;
-                const int f = OUT_F32 ? (row & (CPR - 1)) : ((row >> 1) & (CPR - 1));
-                const uint4 v = *reinterpret_cast<const uint4*>(reg + row * ROWB + ((c ^ f) * 16));
-                const int i = i0 + wm * WTM + pass * ROWS_PER_PASS + row;
-                const int j = j0 + wn * WTN + c * (16 / ESZ);
-                if (i < I) {
-                    uint8_t* p = reinterpret_cast<uint8_t*>(c_out) + ((int64_t)i * ldc + j) * ESZ;
-                    if (j + 16 / ESZ <= J) {
-                        *reinterpret_cast<uint4*>(p) = v;
-                    } else {
-                        const unsigned w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                        for (int e = 0; e < 16 / ESZ; ++e)
-                            if (j + e < J) {
-                                if (OUT_F32) reinterpret_cast<unsigned*>(p)[e] = w[e];
-                                else reinterpret_cast<uint16_t*>(p)[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-                            }
+                for (int it = 0; it < ROWS_PER_PASS / RPI; ++it) {
+                    const int row = it * RPI + lane / CPR;
+                    const int c = lane % CPR;
+                    const int f = OUT_F32 ? (row & (CPR - 1)) : ((row >> 1) & (CPR - 1));
+                    const uint4 v = *reinterpret_cast<const uint4*>(reg + row * ROWB + ((c ^ f) * 16));
+                    const v4u vv = {v.x, v.y, v.z, v.w};
+                    uint8_t* p = const_cast<uint8_t*>(cb) + (int64_t)(it * RPI) * ldc * ESZ + lane_off;
+                    __builtin_nontemporal_store(vv, reinterpret_cast<v4u*>(p));
+                }
+            } else {
+                for (int it = 0; it < ROWS_PER_PASS / RPI; ++it) {
+                    const int row = it * RPI + lane / CPR;
+                    const int c = lane % CPR;
+                    const int f = OUT_F32 ? (row & (CPR - 1)) : ((row >> 1) & (CPR - 1));
+                    const uint4 v = *reinterpret_cast<const uint4*>(reg + row * ROWB + ((c ^ f) * 16));
+                    const int i = i0 + wm * WTM + pass * ROWS_PER_PASS + row;
+                    const int j = j0 + wn * WTN + c * (16 / ESZ);
+                    if (i < I) {
+                        uint8_t* p = reinterpret_cast<uint8_t*>(c_out) + ((int64_t)i * ldc + j) * ESZ;
+                        if (j + 16 / ESZ <= J) {
+                            const v4u vv = {v.x, v.y, v.z, v.w};
+                            __builtin_nontemporal_store(vv, reinterpret_cast<v4u*>(p));
+                        } else {
+                            const unsigned w[4] = {v.x, v.y, v.z, v.w};
+                            for (int e = 0; e < 16 / ESZ; ++e)
+                                if (j + e < J) {
+                                    if (OUT_F32) reinterpret_cast<unsigned*>(p)[e] = w[e];
+                                    else reinterpret_cast<uint16_t*>(p)[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                                }
+                        }
                     }
                 }
             }
         }
+    };
+
+    int u = blockIdx.x;                  // dispatch id of the tile being multiplied
+    int par = 0;                         // buffer of its stage 0
+    bool first = true;
+    set_copy_tile(u);
+    issue(0, 0);
+    int dbg_slot = 0;
+    (void)dbg_slot;
+    SNIP_STAMP(dbg_slot++);
+    for (;;) {
+        const int un = u + (int)gridDim.x;
+        const bool has_next = un < nblk;
+#pragma unroll
+        for (int a = 0; a < MB; ++a)
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int k = 0; k < 16; ++k) acc[a][b][k] = 0.f;
+        const int ebase = ((nstage - 1 + par) & 1) ? C::LDS_BYTES - C::EPI_BYTES : 0;      // over the last stage's buffer
+        if (wave < NWAVE / 2) {
+            // group 0 issues its copies of stage s+1 during M0(s), between b(4s+1) and b(4s+2); during the last
+            // stage these are the copies of the next tile's stage 0
+            auto stage0 = [&](auto copy_tag, int s, int cstage) {
+                const int slot = (s + par) & 1;
+                // stage 0 of a later tile was waited for before the previous tile's result was stored; waiting
+                // here again would wait for those stores
+                if (s > 0 || first) SNIP_WAIT_VM(0);
+                SNIP_BAR();                                         // b(4s)
+                RD(slot, 0); SNIP_BAR();                            // b(4s+1)
+                MM(copy_tag, 0, cstage, slot ^ 1); SNIP_BAR();      // b(4s+2)
+                RD(slot, 1); SNIP_BAR();                            // b(4s+3)
+                MM(no_copy, 1, 0, 0);
+            };
+            // Every stage carries copies, so that the MFMA code exists once (two variants of it merging in front
+            // of the result store cost the register allocator its in-place accumulators).  Without a next tile the
+            // last stage's copies re-fetch stage 0 of this tile into the free buffer, where nobody reads them.
+            for (int s = 0; s < nstage; ++s) {
+                const bool last = s == nstage - 1;
+                if (last && has_next) set_copy_tile(un);
+                stage0(with_copy, s, last ? 0 : s + 1);
+            }
+            SNIP_BAR();                                             // b(4S)
+            SNIP_WAIT_VM(0);                                        // own share of the next tile's stage 0
+        } else {
+            // group 1 issues its copies of stage s+2 during M1(s), between b(4s+4) and b(4s+5) (during M1(S-2)
+            // those of the next tile's stage 0, during M1(S-1) none); those of stage 1 while it idles through the
+            // tile's first phase
+            auto stage1 = [&](auto copy_tag, int s, int cstage) {
+                const int slot = (s + par) & 1;
+                SNIP_BAR();                                         // b(4s+1)
+                RD(slot, 0); SNIP_BAR();                            // b(4s+2)
+                MM(no_copy, 0, 0, 0); SNIP_BAR();                   // b(4s+3)
+                RD(slot, 1);
+                __builtin_amdgcn_s_waitcnt(0x0070);                 // vmcnt(0) and lgkmcnt(0)
+                SNIP_BAR();                                         // b(4s+4)
+                MM(copy_tag, 1, cstage, slot);
+            };
+            if (first) SNIP_WAIT_VM(0);
+            SNIP_BAR();                                             // b(0)
+            issue(1, (1 + par) & 1);
+            // (without a next tile the copies of M1(S-2) re-fetch stage 0 of this tile into the free buffer)
+            for (int s = 0; s < nstage - 1; ++s) {
+                const bool cross = s == nstage - 2;
+                if (cross && has_next) set_copy_tile(un);
+                stage1(with_copy, s, cross ? 0 : s + 2);
+            }
+            stage1(no_copy, nstage - 1, 0);
+        }
+        SNIP_STAMP(dbg_slot++);
+        store_tile(u, ebase);
+        SNIP_STAMP(dbg_slot++);
+        if (!has_next) break;
+        u = un;
+        par = (par + nstage) & 1;
+        first = false;
     }
+#undef SNIP_BAR
+}
+
+// Compute units of the current device, a multiple of 8 (one share per XCD) so that dispatch ids u and u + grid
+// land on the same XCD.
+int compute_units()
+{
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+        cached[dev] = n / 8 * 8;
+    }
+    return cached[dev];
 }
 
 template <int FA, int FB>
 hipError_t launch_fast_t(const GemmArgs& a, hipStream_t s)
 {
     const int ti = (int)((a.I + TM - 1) / TM), tj = (int)((a.J + TN - 1) / TN);
-    const dim3 grid((unsigned)(ti * tj)), block(NT);
+    // one workgroup per compute unit (the LDS array admits no second one), each walking its share of the tiles
+    const int ncu = compute_units();
+    const dim3 grid((unsigned)(ti * tj < ncu ? ti * tj : ncu)), block(NT);
     if (a.out_fp32)
         hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, true>), grid, block, 0, s, a.a_codes, a.a_scales_g4, a.b_codes, a.b_scales_g4,
                            (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj, a.norm_partials);
@@ -465,11 +572,18 @@ hipError_t launch_fast_t(const GemmArgs& a, hipStream_t s)
 
 }  // namespace
 
+#ifdef SNIP_EXP_STAMP
+extern "C" int snip_debug_read(void* host, size_t bytes)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(snip_dbg_stamps), bytes);
+}
+#endif
+
 bool gemm_fast_eligible(const GemmArgs& a)
 {
     const int ke = (a.fmt_a == kFP4 && a.fmt_b == kFP4) ? 256 : 128;
     if (a.R > (1 << 22)) return false;      // per-lane source offsets are 32-bit: 256 rows x row bytes must fit
-    return a.a_scales_g4 && a.b_scales_g4 && a.R % ke == 0 && a.R >= ke && a.I > 128 && a.J > 128;
+    return a.a_scales_g4 && a.b_scales_g4 && a.R % ke == 0 && a.R >= 2 * ke && a.I > 128 && a.J > 128;
 }
 
 int64_t gemm_fast_partials(const GemmArgs& a) { return ((a.I + TM - 1) / TM) * ((a.J + TN - 1) / TN); }
