@@ -1,11 +1,13 @@
 """Benchmark of the SNIP quantized linear-layer hot path on one MI355X.
 
 A step is one pass of the whole path over one Llama-shaped transformer block's seven linear
-layers: every quantization the plan calls for (each distinct (tensor, format, axis) once, with
-the fused error statistics; a tensor wanted in both orientations gets them from one call and one
-read), the 21 GEMMs (fwd, dgrad, wgrad per linear) and the stand-alone statistics pass (both
-formats, both block directions, one read) over every distinct tensor.  Inputs are resident in
-HBM before timing starts.  Prints one JSON line.
+layers: every quantization the plan calls for (each distinct (tensor, format, axis) once; a
+tensor wanted in both orientations gets them from one call and one read) with the statistics
+pass fused into it (the same call returns the squared norms of the tensor and of its
+quantization error for both candidate formats and both block directions: the complete Step-1
+record, no stand-alone statistics launch), and the 21 GEMMs (fwd, dgrad, wgrad per linear).
+A tensor that no two-orientation call covers gets its record from the stand-alone statistics
+call.  Inputs are resident in HBM before timing starts.  Prints one JSON line.
 """
 from __future__ import annotations
 
@@ -23,9 +25,11 @@ import numpy as np
 import torch
 
 PEAK = {"fp4": 10.1e15, "fp8": 5.0e15, "hbm": 8.0e12}
-# L2-miss-side bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated against a copy kernel), measured with
-# rocprofv3 --pmc on this command; see profiles/hbm_traffic_config4_mix50.md.  Keyed by (config, plan, kernel).
-MEASURED_TRAFFIC = {(4, "mix50", "gemm_fast_kernel<fp4,fp4>"): 541.6e6}
+# L2-miss-side bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated against a copy kernel) of the dominant kernel.
+# Not measured by this run: counters need rocprofv3.  The figure is copied from the profile summary named beside
+# it, taken with this command on this kernel; a (config, plan, kernel) without such a profile reports null.
+MEASURED_TRAFFIC = {}
+TRAFFIC_SOURCE = "profiles/hbm_traffic_config4_mix50.md"
 KERNEL_NAME = {(0, 0): "gemm_fast_kernel<fp8,fp8>", (1, 1): "gemm_fast_kernel<fp4,fp4>",
                (0, 1): "gemm_fast_kernel<fp8,fp4>", (1, 0): "gemm_fast_kernel<fp4,fp8>"}
 
@@ -113,6 +117,8 @@ class Layer:
         self.qcalls.sort(key=lambda call: call[0][0][0][0] != "W")        # weights first (stable): their time is reported apart
         # statistics pass: both block directions and both formats of every distinct tensor, one read each
         self.sjobs = [(key, snip.alloc_stats(), snip.alloc_stats()) for key in self.src]
+        covered = {c[0][0][0] for c in self.qcalls if len(c) == 2}
+        self.sjobs_uncovered = [j for j in self.sjobs if j[0] not in covered]
         if output_norms:
             self.gws = torch.empty(max(snip.gemm_workspace_bytes(j[4].shape[0], j[4].shape[1]) for j in self.gjobs),
                                    dtype=torch.uint8, device=dev)
@@ -123,7 +129,7 @@ class Layer:
                            for call in self.qcalls)
         self.s_bytes = sum(self.src[key].numel() * 2 for key, _, _ in self.sjobs)        # one read per tensor
 
-    def step(self, ev=None, fused_statistics=False):
+    def step(self, ev=None, fused_statistics=True):
         snip = self.snip
         fn = {"fwd": snip.snip_gemm_fwd, "dgrad": snip.snip_gemm_dgrad, "wgrad": snip.snip_gemm_wgrad}
 
@@ -156,8 +162,9 @@ class Layer:
                 timed(("g", fmts, fl), lambda: fn_norm[name](pc, a, b, out=out, sum_sq=self.gnorm[gi], workspace=self.gws))
             else:
                 timed(("g", fmts, fl), lambda: fn[name](pc, a, b, out=out))
-        # fused_statistics: every tensor's two-orientation quantize call has delivered the complete record already
-        for key, st_row, st_col in ([] if fused_statistics else self.sjobs):
+        # fused_statistics: a tensor's two-orientation quantize call has delivered its complete record already;
+        # only tensors without such a call (none in configurations 2-5) need the stand-alone statistics call
+        for key, st_row, st_col in (self.sjobs_uncovered if fused_statistics else self.sjobs):
             timed(("s",), lambda: snip.snip_quant_error_stats_both(self.src[key], out_row=st_row, out_col=st_col,
                                                                    workspace=self.ws))
         if ev is not None:
@@ -227,6 +234,9 @@ def kernel_variants(cfg, layer, snip, warm=10, reps=50):
         out[f"quantize_both_{name[fmt]}_stats"] = med_gbps(
             lambda: snip.snip_quantize_both(x, fmt, fmt, out_row=q[snip.ROW], out_col=q[snip.COL], stats_row=st, stats_col=st2,
                                             workspace=layer.ws), both)
+        out[f"quantize_both_{name[fmt]}_stats_both_formats"] = med_gbps(
+            lambda: snip.snip_quantize_both(x, fmt, fmt, out_row=q[snip.ROW], out_col=q[snip.COL], stats_row=st, stats_col=st2,
+                                            workspace=layer.ws, both_formats=True), both)
         del q
     for axis, tag in ((snip.ROW, "row"), (snip.COL, "col")):
         out[f"stats_{tag}"] = med_gbps(lambda: snip.snip_quant_error_stats(x, axis, out=st, workspace=layer.ws), n * 2)
@@ -337,9 +347,12 @@ def library_reference(snip, reps=20):
 
 
 def cpu_baseline(cfg, wl):
-    """The oracle, as it stands, on a bounded sample: the first 256 tokens of the first linear,
-    all three GEMMs with their quantizations (fake-quant + fp64 product)."""
+    """The oracle, as it stands, on bounded samples of this configuration (a baseline for context):
+    GEMM: the first 256 tokens of the first linear, all three GEMMs with their quantizations (fake-quant + fp64
+    product); the full-layer time is EXTRAPOLATED from that slab.  Quantize and statistics: the oracle's
+    quantize (FP4, row blocks) and statistics (both formats, row blocks) in full on the largest tensor."""
     import oracle
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     lin = cfg.linears[0]
     ms = min(256, cfg.M)
     X = wl.make_tensor(cfg, "X", lin.x_group, 0, ms)
@@ -352,10 +365,26 @@ def cpu_baseline(cfg, wl):
     dt = time.time() - t0
     assert y.shape[0] == ms and dx.shape[0] == ms and dw.shape[0] == lin.N
     flops = 3 * 2 * ms * lin.N * lin.K
-    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    layer_flop = sum(3 * 2 * cfg.M * l.N * l.K for l in cfg.linears)
+    # quantize + statistics in full on the largest source tensor of the configuration
+    big = max(cfg.linears, key=lambda l: l.N * l.K)
+    T = wl.make_tensor(cfg, "dY", big.name)
+    t1 = time.time()
+    oracle.quantize(T, oracle.FP4, oracle.ROW)
+    dq = time.time() - t1
+    t1 = time.time()
+    oracle.stats(T, oracle.ROW)
+    ds = time.time() - t1
+    n = T.size
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
             "sample": f"first {ms} tokens of linear '{lin.name}' ({lin.N}x{lin.K}): 3 fake-quant GEMMs in fp64, "
-                      f"{flops:.3g} FLOP in {dt:.2f} s"}
+                      f"{flops:.3g} FLOP in {dt:.2f} s",
+            "gemm_full_layer_seconds_extrapolated": dt * layer_flop / flops,
+            "quantize_gbps": n * (2 + 0.5 + 1 / 32) / dq / 1e9, "quantize_seconds": dq,
+            "stats_gbps": n * 2 / ds / 1e9, "stats_seconds": ds,
+            "quantize_stats_sample": f"dY of '{big.name}' [{T.shape[0]} x {T.shape[1]}] in full: oracle.quantize (FP4, row blocks; "
+                                     f"GB/s of 2 B read + codes + scales written) and oracle.stats (both formats, row blocks; "
+                                     f"GB/s of 2 B read)"}
 
 
 def main():
@@ -410,10 +439,11 @@ def main():
     achieved = dfl / dsec
     gemm_sec = sum(v[0] for v in gem.values()) / args.steps
     q_sec = agg["q"][0] / args.steps
-    s_sec = agg["s"][0] / args.steps
+    s_sec = agg.get("s", [0.0])[0] / args.steps     # stand-alone statistics calls inside the step (none in configs 2-5)
     qw_sec = agg["qw"][0] / args.steps          # quantizations of weights (change once per optimizer step)
     plan_peak = wl.plan_peak_flops(cfg, plan, PEAK["fp4"], PEAK["fp8"])
     value = layer.flops / (ms_per_step * 1e-3) / 1e12
+    traffic = MEASURED_TRAFFIC.get((cfg.index, plan_name, KERNEL_NAME[dom]))
 
     out = {
         "metric": "TFLOP/s of mixed FP4/FP8 fwd+bwd linear GEMMs incl. quantize (% of MFMA peak)",
@@ -421,24 +451,24 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp4_e2m1+fp8_e4m3 (fp32 accumulate, bf16 out)", "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}, {cfg.M} tokens, 7 linears x (fwd, dgrad, wgrad) "
-                               f"+ all quantizations + statistics pass", "plan": plan_name,
+                               f"+ all quantizations with the statistics pass fused into them", "plan": plan_name,
                    "fp4_flop_fraction": wl.plan_fp4_fraction(cfg, plan), "layer_flop": layer.flops,
                    "output_norms": bool(args.output_norms)},
         "pct_of_plan_peak": 100.0 * value * 1e12 / plan_peak,
         "gemm_only_tflops": layer.flops / gemm_sec / 1e12,
         "gemm_only_pct_of_plan_peak": 100.0 * layer.flops / gemm_sec / plan_peak,
+        # quantize calls with the complete statistics record fused in; algorithmic bytes = one read of the source
+        # plus the codes and scales written
         "quantize_gbps": layer.q_bytes / q_sec / 1e9, "quantize_pct_hbm": 100.0 * layer.q_bytes / q_sec / PEAK["hbm"],
-        # the statistics kernel reads a tensor once for both block directions: algorithmic bytes = 2 per element
-        "stats_gbps": layer.s_bytes / s_sec / 1e9, "stats_pct_hbm": 100.0 * layer.s_bytes / s_sec / PEAK["hbm"],
-        "ms_gemm": gemm_sec * 1e3, "ms_quantize": q_sec * 1e3, "ms_stats": s_sec * 1e3,
+        "ms_gemm": gemm_sec * 1e3, "ms_quantize_with_statistics": q_sec * 1e3, "ms_standalone_statistics": s_sec * 1e3,
         "quantized_tensors": len(layer.qjobs), "quantize_calls": len(layer.qcalls),
-        # the two accountings of "incl. quantize" without the stand-alone statistics pass
+        # the two accountings of "incl. quantize"
         "gemm_plus_quantize_tflops": layer.flops / (gemm_sec + q_sec) / 1e12,
         "gemm_plus_quantize_w_amortised_tflops": layer.flops / (gemm_sec + q_sec - qw_sec) / 1e12,
         "input_generation_s": layer.gen_seconds,
         "roofline": {"bound": "mfma", "kernel": KERNEL_NAME[dom], "achieved": achieved / 1e12, "peak": peak / 1e12,
-                     "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": MEASURED_TRAFFIC.get((cfg.index, plan_name, KERNEL_NAME[dom])),
+                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
+                     "traffic_source": TRAFFIC_SOURCE if traffic is not None else None,
                      "launches": dn, "avg_launch_us": dsec / dn * 1e6, "avg_flop_per_launch": dfl / dn},
     }
     # the same step launched the ordinary way without the per-call events of the timed region (on the small
@@ -450,18 +480,30 @@ def main():
     torch.cuda.synchronize()
     ms_plain = (time.perf_counter() - t1) / args.steps * 1e3
     out["no_events"] = {"ms_per_step": ms_plain, "value": layer.flops / (ms_plain * 1e-3) / 1e12, "unit": "TFLOP/s"}
-    # Not `value`: the same outputs with the statistics pass folded into the quantize calls (each tensor's call for
-    # both orientations also returns the error sums of both formats), i.e. no stand-alone statistics launches.
-    if all(any(len(c) == 2 and c[0][0][0] == key for c in layer.qcalls) for key in layer.src) and not args.separate_quantize:
-        for _ in range(2):
-            layer.step(fused_statistics=True)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for _ in range(args.steps):
-            layer.step(fused_statistics=True)
-        torch.cuda.synchronize()
-        ms_f = (time.perf_counter() - t1) / args.steps * 1e3
-        out["statistics_fused_into_quantize"] = {"ms_per_step": ms_f, "value": layer.flops / (ms_f * 1e-3) / 1e12, "unit": "TFLOP/s"}
+    # Not `value`: the same outputs with the statistics as a pass of its own (every quantize call returns the error of
+    # the format it writes, a stand-alone call per tensor reads it again for both formats and both block directions).
+    sep_ev = []
+    for _ in range(2):
+        layer.step(fused_statistics=False)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        layer.step(sep_ev, fused_statistics=False)
+    torch.cuda.synchronize()
+    ms_f = (time.perf_counter() - t1) / args.steps * 1e3
+    sq = ss = 0.0
+    for (tag, a), (_, b) in zip(sep_ev[:-1], sep_ev[1:]):
+        if tag[0] == "q":
+            sq += a.elapsed_time(b) * 1e-3
+        elif tag[0] == "s":
+            ss += a.elapsed_time(b) * 1e-3
+    sq /= args.steps
+    ss /= args.steps
+    out["statistics_as_separate_pass"] = {
+        "ms_per_step": ms_f, "value": layer.flops / (ms_f * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "ms_quantize": sq * 1e3, "quantize_gbps": layer.q_bytes / sq / 1e9 if sq else None,
+        "ms_stats": ss * 1e3, "stats_gbps": layer.s_bytes / ss / 1e9 if ss else None,
+        "stats_pct_hbm": 100.0 * layer.s_bytes / ss / PEAK["hbm"] if ss else None}
     if not args.no_graph:
         out["hip_graph"] = graph_replay(layer, args.steps, args.warmup)
     if not args.no_next_rows:

@@ -83,7 +83,8 @@ typedef enum {
  *           [ceil(cols/128)][rows_pad][4], i.e. the four scales of 128 consecutive contraction
  *           elements of a row in one dword, rows contiguous; rows_pad = rows rounded up to a
  *           multiple of 256 (dwords of rows >= `rows`, and bytes of blocks >= cols/32, are
- *           unspecified).  4-byte aligned.  snip_quantize fills it when it is not NULL; when both
+ *           unspecified).  16-byte aligned (the quantize kernels write it with 16-byte stores;
+ *           SNIP_ERR_LAYOUT otherwise).  snip_quantize fills it when it is not NULL; when both
  *           operands of a GEMM carry one and cols is a multiple of 128 the GEMM copies its scales
  *           from it with fully coalesced loads, otherwise it falls back to a slower kernel that
  *           gathers from `scales`.  Size: snip_qtensor_scale_g4_bytes.
@@ -105,7 +106,14 @@ typedef struct {
 
 /* Squared Frobenius norms (Sec. 3.1 Step 1): of the tensor, and of q(x) - x for both candidate
  * formats.  A fused quantize call fills sum_sq and the chosen format's field and writes NaN
- * into the other. */
+ * into the other.
+ * Range: differences are exact and squares are formed and added per lane in fp32 (wave and
+ * workgroup partials in fp32, everything above in double), so the stated 1e-5 relative accuracy
+ * holds for tensors whose nonzero magnitudes lie within [2^-56, 2^48]: below, the squares of
+ * the errors (about 2^-5 |x| for FP8) leave the fp32 normal range and count as less than they
+ * are; above, sums of squares overflow to infinity.  A lane adds at most rows / 64 (column
+ * blocks) or cols / 8 (row blocks) groups of 8 squares before its sum moves to the next level,
+ * which keeps the rounding of a sum of n equal terms below 1e-5 up to about 2^22 rows. */
 typedef struct { double sum_sq, err_sq_fp4, err_sq_fp8; } snip_stats;
 
 /* ---- sizes (host, pure) ------------------------------------------------------------- */

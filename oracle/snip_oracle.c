@@ -525,8 +525,10 @@ double oracle_weight_divergence(double alpha, double beta1, double beta2, int64_
  * value the GEMM sees is y / scale.  Sec. 5.1: the groups are 1x128 tiles for activations and
  * gradients and 128x128 blocks for weights.  Unlike the power-of-two block scales above, this
  * scale is a real number and x * scale is not exact, so the precision of those two steps is
- * part of the definition; it is fp32 here (one correctly rounded division, one correctly
- * rounded product), the working precision of the GPU path:
+ * part of the definition.  The paper gives the formula, not the arithmetic; its experiments
+ * fake-quantize inside a training framework (Sec. 5.1), where such a scale is held as an fp32
+ * tensor and multiplied in fp32.  The reading taken here is therefore fp32: one correctly
+ * rounded division, one correctly rounded product:
  *     s = (float)FPX_MAX / amax          (amax = 0: s = 1;  s is capped at 2^126 so that a
  *                                         group of denormal-sized values does not overflow it)
  *     t = (float)x * s

@@ -42,7 +42,7 @@ snip_status check_qtensor(const snip_qtensor* q)
     if (q->rows < 0 || q->cols <= 0 || q->cols % 32 != 0) return SNIP_ERR_SHAPE;
     if (q->rows >= (int64_t)1 << 31 || q->cols >= (int64_t)1 << 31) return SNIP_ERR_SHAPE;
     if (!aligned16(q->codes)) return SNIP_ERR_LAYOUT;
-    if (q->scales_g4 && (reinterpret_cast<uintptr_t>(q->scales_g4) & 3u)) return SNIP_ERR_LAYOUT;
+    if (q->scales_g4 && !aligned16(q->scales_g4)) return SNIP_ERR_LAYOUT;      // written with 16-byte stores
     if (reinterpret_cast<uintptr_t>(q->scales) & 3u) return SNIP_ERR_LAYOUT;
     return SNIP_OK;
 }
@@ -123,7 +123,7 @@ snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
     const int64_t sr = axis == SNIP_AXIS_ROW ? rows : cols, sc = axis == SNIP_AXIS_ROW ? cols : rows;
     if (out->rows != sr || out->cols != sc) return SNIP_ERR_SHAPE;
     if (!aligned16(out->codes)) return SNIP_ERR_LAYOUT;
-    if (out->scales_g4 && (reinterpret_cast<uintptr_t>(out->scales_g4) & 3u)) return SNIP_ERR_LAYOUT;
+    if (out->scales_g4 && !aligned16(out->scales_g4)) return SNIP_ERR_LAYOUT;
     if (reinterpret_cast<uintptr_t>(out->scales) & 3u) return SNIP_ERR_LAYOUT;
     if (stats) {
         if (!workspace || workspace_bytes_ < workspace_bytes(rows, cols)) return SNIP_ERR_WORKSPACE;
@@ -156,7 +156,7 @@ snip_status snip_quantize_both(const void* x, int64_t rows, int64_t cols, int64_
         if (!valid_fmt((snip_fmt)o->fmt)) return SNIP_ERR_FORMAT;
         if (o->rows != (i == 0 ? rows : cols) || o->cols != (i == 0 ? cols : rows)) return SNIP_ERR_SHAPE;
         if (!aligned16(o->codes)) return SNIP_ERR_LAYOUT;
-        if (o->scales_g4 && (reinterpret_cast<uintptr_t>(o->scales_g4) & 3u)) return SNIP_ERR_LAYOUT;
+        if (o->scales_g4 && !aligned16(o->scales_g4)) return SNIP_ERR_LAYOUT;
         if (reinterpret_cast<uintptr_t>(o->scales) & 3u) return SNIP_ERR_LAYOUT;
     }
     if (stats_row) {
@@ -183,7 +183,7 @@ snip_status snip_quantize_sr_fp4(const void* x, int64_t rows, int64_t cols, int6
     const int64_t sr = axis == SNIP_AXIS_ROW ? rows : cols, sc = axis == SNIP_AXIS_ROW ? cols : rows;
     if (out->rows != sr || out->cols != sc) return SNIP_ERR_SHAPE;
     if (!aligned16(out->codes)) return SNIP_ERR_LAYOUT;
-    if (out->scales_g4 && (reinterpret_cast<uintptr_t>(out->scales_g4) & 3u)) return SNIP_ERR_LAYOUT;
+    if (out->scales_g4 && !aligned16(out->scales_g4)) return SNIP_ERR_LAYOUT;
     if (reinterpret_cast<uintptr_t>(out->scales) & 3u) return SNIP_ERR_LAYOUT;
     QuantArgs a;
     a.x = (const uint16_t*)x; a.rows = rows; a.cols = cols; a.ld = ld;

@@ -130,6 +130,22 @@ def _stream(stream) -> int:
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
+def _alloc_on(stream):
+    """Context for the temporaries a wrapper allocates itself (outputs, workspaces): they must belong to the stream
+    the kernels run on, or the caching allocator may hand them to other work of the current stream while the kernels
+    still use them.  A torch stream is entered; a raw stream handle other than the current stream's cannot be
+    (torch cannot allocate on it), so such callers pass every buffer themselves."""
+    import contextlib
+    if stream is None:
+        return contextlib.nullcontext()
+    if isinstance(stream, torch.cuda.Stream):
+        return torch.cuda.stream(stream)
+    if int(stream) != torch.cuda.current_stream().cuda_stream:
+        raise ValueError("a raw stream handle that is not the current torch stream was given and a buffer would have to be "
+                         "allocated: pass out / workspace / statistics buffers explicitly, or pass a torch.cuda.Stream")
+    return contextlib.nullcontext()
+
+
 def _check(status: int, where: str):
     if status != 0:
         raise SnipError(status, where)
@@ -202,11 +218,13 @@ def snip_quantize(x: torch.Tensor, fmt: int, axis: int = ROW, rule: int = NO_OVE
                   out: Optional[QTensor] = None, stats: Optional[torch.Tensor] = None,
                   workspace: Optional[torch.Tensor] = None, stream=None) -> QTensor:
     ptr, rows, cols, ld = _src(x)
-    if out is None:
-        sr, sc = (rows, cols) if axis == ROW else (cols, rows)
-        out = alloc_qtensor(sr, sc, fmt, x.device)
-    if stats is not None and workspace is None:
-        workspace = alloc_workspace(rows, cols, x.device)
+    if out is None or (stats is not None and workspace is None):
+        with _alloc_on(stream):
+            if out is None:
+                sr, sc = (rows, cols) if axis == ROW else (cols, rows)
+                out = alloc_qtensor(sr, sc, fmt, x.device)
+            if stats is not None and workspace is None:
+                workspace = alloc_workspace(rows, cols, x.device)
     q = out.c_struct()
     _check(_lib().snip_quantize(ptr, rows, cols, ld, fmt, axis, rule, ctypes.byref(q),
                                 stats.data_ptr() if stats is not None else None,
@@ -223,12 +241,14 @@ def snip_quantize_both(x: torch.Tensor, fmt_row: int, fmt_col: int, rule: int = 
     """Row-block and column-block quantization of x from one read; returns (out_row, out_col).  With statistics
     outputs and both_formats=True they receive the error sums of both formats, not only of the ones written."""
     ptr, rows, cols, ld = _src(x)
-    if out_row is None:
-        out_row = alloc_qtensor(rows, cols, fmt_row, x.device)
-    if out_col is None:
-        out_col = alloc_qtensor(cols, rows, fmt_col, x.device)
-    if stats_row is not None and workspace is None:
-        workspace = alloc_workspace(rows, cols, x.device)
+    if out_row is None or out_col is None or (stats_row is not None and workspace is None):
+        with _alloc_on(stream):
+            if out_row is None:
+                out_row = alloc_qtensor(rows, cols, fmt_row, x.device)
+            if out_col is None:
+                out_col = alloc_qtensor(cols, rows, fmt_col, x.device)
+            if stats_row is not None and workspace is None:
+                workspace = alloc_workspace(rows, cols, x.device)
     qr, qc = out_row.c_struct(), out_col.c_struct()
     _check(_lib().snip_quantize_both(ptr, rows, cols, ld, rule, ctypes.byref(qr), ctypes.byref(qc),
                                      stats_row.data_ptr() if stats_row is not None else None,
@@ -245,8 +265,9 @@ def snip_quantize_sr_fp4(x: torch.Tensor, axis: int = ROW, rule: int = NO_OVERFL
     """FP4 quantization with stochastic rounding; `seed` (64 bit) selects the random byte stream."""
     ptr, rows, cols, ld = _src(x)
     if out is None:
-        sr, sc = (rows, cols) if axis == ROW else (cols, rows)
-        out = alloc_qtensor(sr, sc, FP4, x.device)
+        with _alloc_on(stream):
+            sr, sc = (rows, cols) if axis == ROW else (cols, rows)
+            out = alloc_qtensor(sr, sc, FP4, x.device)
     q = out.c_struct()
     _check(_lib().snip_quantize_sr_fp4(ptr, rows, cols, ld, axis, rule, int(seed) & (2 ** 64 - 1), ctypes.byref(q),
                                        _stream(stream)), "snip_quantize_sr_fp4")
@@ -260,10 +281,11 @@ def snip_quantize_paper(x: torch.Tensor, fmt: int, axis: int = ROW, group: int =
     """The paper's recipe: returns (codes uint8 [SR, SC or SC/2], scales float32 [SR or ceil(SR/128), SC/128])."""
     ptr, rows, cols, ld = _src(x)
     sr, sc = (rows, cols) if axis == ROW else (cols, rows)
-    codes = torch.empty((sr, sc if fmt == FP8 else sc // 2), dtype=torch.uint8, device=x.device)
     nbytes = int(_lib().snip_paper_scale_bytes(sr, sc, group))
-    scales = torch.empty((nbytes // 4 // max(1, sc // 128), sc // 128) if sc >= 128 else (0, 0), dtype=torch.float32,
-                         device=x.device)
+    with _alloc_on(stream):
+        codes = torch.empty((sr, sc if fmt == FP8 else sc // 2), dtype=torch.uint8, device=x.device)
+        scales = torch.empty((nbytes // 4 // max(1, sc // 128), sc // 128) if sc >= 128 else (0, 0), dtype=torch.float32,
+                             device=x.device)
     _check(_lib().snip_quantize_paper(ptr, rows, cols, ld, fmt, axis, group, codes.data_ptr() if codes.numel() else None,
                                       scales.data_ptr() if scales.numel() else None, _stream(stream)), "snip_quantize_paper")
     return codes, scales
@@ -274,12 +296,14 @@ def snip_quant_error_stats_both(x: torch.Tensor, rule: int = NO_OVERFLOW, out_ro
                                 stream=None):
     """Statistics for both block directions from one read; returns (out_row, out_col)."""
     ptr, rows, cols, ld = _src(x)
-    if out_row is None:
-        out_row = alloc_stats(x.device)
-    if out_col is None:
-        out_col = alloc_stats(x.device)
-    if workspace is None:
-        workspace = alloc_workspace(rows, cols, x.device)
+    if out_row is None or out_col is None or workspace is None:
+        with _alloc_on(stream):
+            if out_row is None:
+                out_row = alloc_stats(x.device)
+            if out_col is None:
+                out_col = alloc_stats(x.device)
+            if workspace is None:
+                workspace = alloc_workspace(rows, cols, x.device)
     _check(_lib().snip_quant_error_stats_both(ptr, rows, cols, ld, rule, out_row.data_ptr(), out_col.data_ptr(),
                                               workspace.data_ptr(), workspace.numel(), _stream(stream)),
            "snip_quant_error_stats_both")
@@ -296,8 +320,9 @@ def snip_gemm_paper(a_codes, a_scales, a_fmt, a_group, b_codes, b_scales, b_fmt,
                          rows, cols, fmt, group)
     pa, pb = pt(a_codes, a_scales, a_fmt, a_group), pt(b_codes, b_scales, b_fmt, b_group)
     if out is None:
-        out = torch.empty((pa.rows, pb.rows), dtype=torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32,
-                          device=a_codes.device)
+        with _alloc_on(stream):
+            out = torch.empty((pa.rows, pb.rows), dtype=torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32,
+                              device=a_codes.device)
     _check(_lib().snip_gemm_paper(ctypes.byref(pa), ctypes.byref(pb), out.data_ptr(), out.stride(0), out_dtype,
                                   _stream(stream)), "snip_gemm_paper")
     return out
@@ -307,10 +332,12 @@ def snip_quant_error_stats_paper(x: torch.Tensor, axis: int = ROW, group: int = 
                                  out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                                  stream=None) -> torch.Tensor:
     ptr, rows, cols, ld = _src(x)
-    if out is None:
-        out = alloc_stats(x.device)
-    if workspace is None:
-        workspace = torch.empty(int(_lib().snip_paper_workspace_bytes(rows, cols)), dtype=torch.uint8, device=x.device)
+    if out is None or workspace is None:
+        with _alloc_on(stream):
+            if out is None:
+                out = alloc_stats(x.device)
+            if workspace is None:
+                workspace = torch.empty(int(_lib().snip_paper_workspace_bytes(rows, cols)), dtype=torch.uint8, device=x.device)
     _check(_lib().snip_quant_error_stats_paper(ptr, rows, cols, ld, axis, group, out.data_ptr(), workspace.data_ptr(),
                                                workspace.numel(), _stream(stream)), "snip_quant_error_stats_paper")
     return out
@@ -322,10 +349,12 @@ def snip_adamw_sensitivity(m: torch.Tensor, v: torch.Tensor, g: torch.Tensor, be
     """Squared Frobenius norm of dh/dg of the AdamW update direction; m, v fp32, g fp32 or bf16, contiguous."""
     assert m.dtype == torch.float32 and v.dtype == torch.float32 and g.dtype in (torch.float32, torch.bfloat16)
     assert m.is_contiguous() and v.is_contiguous() and g.is_contiguous() and m.numel() == v.numel() == g.numel()
-    if out is None:
-        out = torch.empty(1, dtype=torch.float64, device=m.device)
-    if workspace is None:
-        workspace = alloc_workspace(0, 0, m.device)
+    if out is None or workspace is None:
+        with _alloc_on(stream):
+            if out is None:
+                out = torch.empty(1, dtype=torch.float64, device=m.device)
+            if workspace is None:
+                workspace = alloc_workspace(0, 0, m.device)
     n = m.numel()
     _check(_lib().snip_adamw_sensitivity(m.data_ptr() if n else None, v.data_ptr() if n else None,
                                          g.data_ptr() if n else None,
@@ -346,8 +375,9 @@ def _gemm(fn_name: str, plan, a: QTensor, b: QTensor, out, out_dtype, stream):
     if not isinstance(plan, _PlanC):
         plan = make_plan(plan)
     if out is None:
-        out = torch.empty((a.rows, b.rows), dtype=torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32,
-                          device=a.codes.device)
+        with _alloc_on(stream):
+            out = torch.empty((a.rows, b.rows), dtype=torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32,
+                              device=a.codes.device)
     qa, qb = a.c_struct(), b.c_struct()
     _check(getattr(_lib(), fn_name)(ctypes.byref(plan), ctypes.byref(qa), ctypes.byref(qb), out.data_ptr(),
                                     out.stride(0), out_dtype, None, 0, _stream(stream)), fn_name)
@@ -362,12 +392,14 @@ def _gemm_norm(fn_name, plan, a: QTensor, b: QTensor, out, out_dtype, sum_sq, wo
     if not isinstance(plan, _PlanC):
         plan = make_plan(plan)
     dt = torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32
-    if out is None:
-        out = torch.empty((a.rows, b.rows), dtype=dt, device=a.codes.device)
-    if sum_sq is None:
-        sum_sq = torch.empty(1, dtype=torch.float64, device=a.codes.device)
-    if workspace is None:
-        workspace = torch.empty(gemm_workspace_bytes(a.rows, b.rows), dtype=torch.uint8, device=a.codes.device)
+    if out is None or sum_sq is None or workspace is None:
+        with _alloc_on(stream):
+            if out is None:
+                out = torch.empty((a.rows, b.rows), dtype=dt, device=a.codes.device)
+            if sum_sq is None:
+                sum_sq = torch.empty(1, dtype=torch.float64, device=a.codes.device)
+            if workspace is None:
+                workspace = torch.empty(gemm_workspace_bytes(a.rows, b.rows), dtype=torch.uint8, device=a.codes.device)
     qa, qb = a.c_struct(), b.c_struct()
     _check(getattr(_lib(), fn_name)(ctypes.byref(plan), ctypes.byref(qa), ctypes.byref(qb),
                                     out.data_ptr(), out.stride(0), out_dtype, sum_sq.data_ptr(), workspace.data_ptr(),
@@ -416,10 +448,12 @@ def snip_quant_error_stats(x: torch.Tensor, axis: int = ROW, rule: int = NO_OVER
                            out: Optional[torch.Tensor] = None, per_line: Optional[torch.Tensor] = None,
                            workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     ptr, rows, cols, ld = _src(x)
-    if out is None:
-        out = alloc_stats(x.device)
-    if workspace is None:
-        workspace = alloc_workspace(rows, cols, x.device)
+    if out is None or workspace is None:
+        with _alloc_on(stream):
+            if out is None:
+                out = alloc_stats(x.device)
+            if workspace is None:
+                workspace = alloc_workspace(rows, cols, x.device)
     _check(_lib().snip_quant_error_stats(ptr, rows, cols, ld, axis, rule, out.data_ptr(),
                                          per_line.data_ptr() if per_line is not None else None,
                                          workspace.data_ptr(), workspace.numel(), _stream(stream)),

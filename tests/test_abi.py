@@ -64,6 +64,17 @@ def test_validation_rejects_before_launch():
     assert L.snip_status_string(4).decode().startswith("bad alignment")
 
 
+def test_grouped_scale_copy_must_be_16_byte_aligned():
+    snip = lib()
+    L = snip._lib()
+    fake = ctypes.c_void_p(0x1000)
+    q = snip._QTensorC(0x1000, 0x1000, 0x1004, 32, 64, 0)          # grouped copy only 4-byte aligned
+    assert L.snip_quantize(fake, 32, 64, 64, 0, 0, 0, ctypes.byref(q), None, None, 0, None) == 4
+    plan = snip.make_plan((0,) * 6)
+    ok = snip._QTensorC(0x1000, 0x1000, 0x1000, 32, 64, 0)
+    assert L.snip_gemm_fwd(ctypes.byref(plan), ctypes.byref(q), ctypes.byref(ok), fake, 64, 0, None, 0, None) == 4
+
+
 def test_quantize_both_validation():
     snip = lib()
     L = snip._lib()

@@ -147,3 +147,22 @@ def test_stats_both_special_cases():
     r, c = snip.snip_quant_error_stats_both(e)
     torch.cuda.synchronize()
     assert host(r).tolist() == [0.0, 0.0, 0.0] and host(c).tolist() == [0.0, 0.0, 0.0]
+
+
+@pytest.mark.parametrize("shift", [-40, 40])
+def test_stats_at_the_ends_of_the_documented_magnitude_range(shift):
+    """Tensors scaled by 2^-40 and 2^40: differences stay exact and the fp32 squares stay normal, so the
+    statistics keep their tolerance against the oracle's fp64 sums (both directions, one-read variant too)."""
+    snip = require_gpu()
+    rng = np.random.default_rng(33)
+    a = rng.standard_normal((256, 640)) * 2.0 ** shift
+    bits = wl.f32_to_bf16_bits(a.astype(np.float32))
+    for axis in (oracle.ROW, oracle.COL):
+        got, got_lines = run(snip, bits, axis, oracle.NO_OVERFLOW)
+        want, want_lines = oracle.stats(bits, axis, oracle.NO_OVERFLOW, per_line=True)
+        np.testing.assert_allclose(got, want, rtol=TOL)
+        np.testing.assert_allclose(got_lines, want_lines, rtol=TOL, atol=0)
+    r, c = snip.snip_quant_error_stats_both(to_dev(bits))
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(host(r), oracle.stats(bits, oracle.ROW), rtol=TOL)
+    np.testing.assert_allclose(host(c), oracle.stats(bits, oracle.COL), rtol=TOL)

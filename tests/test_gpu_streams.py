@@ -43,3 +43,31 @@ def test_two_streams_with_their_own_workspaces():
         assert torch.equal(g[0].scales, r[0].scales) and torch.equal(g[1].scales, r[1].scales)
         assert host(g[2]).tobytes() == host(r[2]).tobytes() and host(g[3]).tobytes() == host(r[3]).tobytes()
         assert torch.equal(g[4], r[4])
+
+
+def test_temporaries_belong_to_the_stream_of_the_call():
+    """A call on a side stream that lets the wrapper allocate its workspace and outputs: the temporaries are taken
+    from that stream's pool (so the current stream's work cannot be handed the workspace while the side stream's
+    kernels still use it), and a raw handle of a foreign stream is refused when a buffer would have to be allocated."""
+    snip = require_gpu()
+    rng = np.random.default_rng(78)
+    x = to_dev(wl.f32_to_bf16_bits(rng.standard_normal((1024, 1024)).astype(np.float32)))
+    ref = snip.snip_quant_error_stats(x, snip.COL)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    outs = []
+    for _ in range(8):
+        outs.append(snip.snip_quant_error_stats(x, snip.COL, stream=side))       # workspace + output allocated inside
+        torch.empty(1 << 22, dtype=torch.uint8, device="cuda").fill_(0xFF)      # current-stream work wanting memory
+    side.synchronize()
+    torch.cuda.synchronize()
+    for o in outs:
+        assert host(o).tobytes() == host(ref).tobytes()
+    with pytest.raises(ValueError):
+        snip.snip_quant_error_stats(x, snip.COL, stream=side.cuda_stream)        # raw handle, would allocate
+    ws, out = snip.alloc_workspace(1024, 1024), snip.alloc_stats()
+    side.wait_stream(torch.cuda.current_stream())
+    snip.snip_quant_error_stats(x, snip.COL, out=out, workspace=ws, stream=side.cuda_stream)   # raw handle, nothing to allocate
+    side.synchronize()
+    assert host(out).tobytes() == host(ref).tobytes()
