@@ -33,6 +33,7 @@
 // See gemm.hip for the register layout of v_mfma_scale_f32_32x32x64_f8f6f4.
 #include "snip_internal.h"
 #include <type_traits>
+#include <cstdlib>
 
 namespace snip {
 namespace {
@@ -134,13 +135,6 @@ __device__ __forceinline__ v8i read_frag(const uint8_t* tile, int rowblock_off, 
     return f;
 }
 
-#ifdef SNIP_EXP_STAMP
-__device__ unsigned long long snip_dbg_stamps[64 * 8 * 16];      // [block < 64][wave][slot]
-#define SNIP_STAMP(slot) do { const int sl_ = (slot); if (blockIdx.x < 64 && lane == 0 && sl_ < 16) snip_dbg_stamps[(blockIdx.x * 8 + wave) * 16 + sl_] = wall_clock64(); } while (0)
-#else
-#define SNIP_STAMP(slot) do { } while (0)
-#endif
-
 // Dispatch id -> tile.  Workgroups are dealt round-robin to the 8 XCDs, so ids u, u + 8, u + 16, ... share an L2:
 // each XCD gets a contiguous run of the tile sequence, and the sequence walks bands of 4 tile rows column by
 // column, so that the 32 tiles an XCD works on at a time are a 4 x 8 patch (4 + 8 operand slabs for 32 tiles).
@@ -164,7 +158,8 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                                                        const uint8_t* __restrict__ b_codes,
                                                        const uint8_t* __restrict__ b_g4,
                                                        int I, int J, int R, void* __restrict__ c_out, int64_t ldc,
-                                                       int tiles_i, int tiles_j, float* __restrict__ norm_partials)
+                                                       int tiles_i, int tiles_j, float* __restrict__ norm_partials,
+                                                       int stream_out)
 {
     using C = FCfg<FA, FB>;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[C::LDS_BYTES];
@@ -414,9 +409,11 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                         }
                     }
             }
-            // read back row-contiguous: 64 lanes cover 64 / CPR rows per instruction.  Streaming stores: all
-            // workgroups finish a tile at about the same time (32 MB per round of tiles, the size of all L2s
-            // together); lines that nobody here reads again should not push the operands out of the caches.
+            // read back row-contiguous: 64 lanes cover 64 / CPR rows per instruction.  All workgroups finish a tile
+            // at about the same time: 32 MB per round of tiles, the size of all L2s together.  When operands and
+            // output together fit the memory-side cache, plain stores are absorbed there fastest (2.1-2.7 us per tile
+            // for the later group of waves against 3-5 us); when they do not, streaming stores keep the output from
+            // pushing the operands out (8-10 % on the FP8 GEMMs with 180 MB operands).  The launcher decides.
             constexpr int RPI = 64 / CPR;
             if (interior) {
                 // whole tile inside the matrix (wave-uniform): no per-lane tests, one wave-uniform base per
@@ -432,7 +429,8 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                     const uint4 v = *reinterpret_cast<const uint4*>(reg + row * ROWB + ((c ^ f) * 16));
                     const v4u vv = {v.x, v.y, v.z, v.w};
                     uint8_t* p = const_cast<uint8_t*>(cb) + (int64_t)(it * RPI) * ldc * ESZ + lane_off;
-                    __builtin_nontemporal_store(vv, reinterpret_cast<v4u*>(p));
+                    if (stream_out) __builtin_nontemporal_store(vv, reinterpret_cast<v4u*>(p));
+                    else *reinterpret_cast<v4u*>(p) = vv;
                 }
             } else {
                 for (int it = 0; it < ROWS_PER_PASS / RPI; ++it) {
@@ -445,8 +443,7 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                     if (i < I) {
                         uint8_t* p = reinterpret_cast<uint8_t*>(c_out) + ((int64_t)i * ldc + j) * ESZ;
                         if (j + 16 / ESZ <= J) {
-                            const v4u vv = {v.x, v.y, v.z, v.w};
-                            __builtin_nontemporal_store(vv, reinterpret_cast<v4u*>(p));
+                            *reinterpret_cast<uint4*>(p) = v;
                         } else {
                             const unsigned w[4] = {v.x, v.y, v.z, v.w};
                             for (int e = 0; e < 16 / ESZ; ++e)
@@ -466,9 +463,6 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
     bool first = true;
     set_copy_tile(u);
     issue(0, 0);
-    int dbg_slot = 0;
-    (void)dbg_slot;
-    SNIP_STAMP(dbg_slot++);
     for (;;) {
         const int un = u + (int)gridDim.x;
         const bool has_next = un < nblk;
@@ -488,9 +482,9 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                 // here again would wait for those stores
                 if (s > 0 || first) SNIP_WAIT_VM(0);
                 SNIP_BAR();                                         // b(4s)
-                RD(slot, 0); SNIP_BAR();                            // b(4s+1)
+                RD(slot, 0); SNIP_BAR();         // b(4s+1)
                 MM(copy_tag, 0, cstage, slot ^ 1); SNIP_BAR();      // b(4s+2)
-                RD(slot, 1); SNIP_BAR();                            // b(4s+3)
+                RD(slot, 1); SNIP_BAR();         // b(4s+3)
                 MM(no_copy, 1, 0, 0);
             };
             // Every stage carries copies, so that the MFMA code exists once (two variants of it merging in front
@@ -510,7 +504,7 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
             auto stage1 = [&](auto copy_tag, int s, int cstage) {
                 const int slot = (s + par) & 1;
                 SNIP_BAR();                                         // b(4s+1)
-                RD(slot, 0); SNIP_BAR();                            // b(4s+2)
+                RD(slot, 0); SNIP_BAR();         // b(4s+2)
                 MM(no_copy, 0, 0, 0); SNIP_BAR();                   // b(4s+3)
                 RD(slot, 1);
                 __builtin_amdgcn_s_waitcnt(0x0070);                 // vmcnt(0) and lgkmcnt(0)
@@ -528,9 +522,7 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
             }
             stage1(no_copy, nstage - 1, 0);
         }
-        SNIP_STAMP(dbg_slot++);
         store_tile(u, ebase);
-        SNIP_STAMP(dbg_slot++);
         if (!has_next) break;
         u = un;
         par = (par + nstage) & 1;
@@ -561,23 +553,21 @@ hipError_t launch_fast_t(const GemmArgs& a, hipStream_t s)
     // one workgroup per compute unit (the LDS array admits no second one), each walking its share of the tiles
     const int ncu = compute_units();
     const dim3 grid((unsigned)(ti * tj < ncu ? ti * tj : ncu)), block(NT);
+    // streaming output stores when operands + output exceed what the memory-side cache (256 MB) can hold next to
+    // everything else in flight
+    const double bytes = (double)a.I * a.R * (FA == kFP8 ? 1.0 : 0.5) + (double)a.J * a.R * (FB == kFP8 ? 1.0 : 0.5) +
+                         (double)a.I * a.J * (a.out_fp32 ? 4.0 : 2.0);
+    int stream_out = bytes > 200e6;
     if (a.out_fp32)
         hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, true>), grid, block, 0, s, a.a_codes, a.a_scales_g4, a.b_codes, a.b_scales_g4,
-                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj, a.norm_partials);
+                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj, a.norm_partials, stream_out);
     else
         hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, false>), grid, block, 0, s, a.a_codes, a.a_scales_g4, a.b_codes, a.b_scales_g4,
-                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj, a.norm_partials);
+                           (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj, a.norm_partials, stream_out);
     return hipGetLastError();
 }
 
 }  // namespace
-
-#ifdef SNIP_EXP_STAMP
-extern "C" int snip_debug_read(void* host, size_t bytes)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(snip_dbg_stamps), bytes);
-}
-#endif
 
 bool gemm_fast_eligible(const GemmArgs& a)
 {

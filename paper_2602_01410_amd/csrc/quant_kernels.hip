@@ -97,12 +97,22 @@ __device__ __forceinline__ unsigned clamp_fp8(unsigned w, unsigned byte)
     return mag | (w & 0x80008000u);
 }
 
+// A register with unspecified content, at no cost: the packing conversions below replace their destination piece by
+// piece (two halves for FP8, four bytes for FP4) and keep the rest, so the value they start from never survives;
+// starting from zero would cost a move per destination.
+__device__ __forceinline__ unsigned any_value()
+{
+    unsigned r;
+    asm volatile("" : "=v"(r));
+    return r;
+}
+
 // Two bf16 pairs (4 elements) -> 4 FP8 bytes.
 template <int RULE>
 __device__ __forceinline__ unsigned enc8(unsigned w0, unsigned w1, float sc, unsigned byte)
 {
     if (RULE == 1) { w0 = clamp_fp8(w0, byte); w1 = clamp_fp8(w1, byte); }
-    short2_t r = {0, 0};
+    short2_t r = __builtin_bit_cast(short2_t, any_value());
     r = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(r, __builtin_bit_cast(bf16x2, w0), sc, false);
     r = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(r, __builtin_bit_cast(bf16x2, w1), sc, true);
     return __builtin_bit_cast(unsigned, r);
@@ -111,7 +121,7 @@ __device__ __forceinline__ unsigned enc8(unsigned w0, unsigned w1, float sc, uns
 // Four bf16 pairs (8 elements) -> 8 FP4 nibbles, element 0 in the lowest nibble.
 __device__ __forceinline__ unsigned enc4(unsigned w0, unsigned w1, unsigned w2, unsigned w3, float sc)
 {
-    unsigned r = 0;
+    unsigned r = any_value();
     r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(bf16x2, w0), sc, 0);
     r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(bf16x2, w1), sc, 1);
     r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(bf16x2, w2), sc, 2);
