@@ -196,7 +196,12 @@ snip_status snip_quantize_sr_fp4(const void* x, int64_t rows, int64_t cols, int6
  *
  *   fwd  : Xq  = quantize(X,  ROW) [M,K],  Wq  = quantize(W,  ROW) [N,K]  ->  Y  [M,N]
  *   dgrad: dYq = quantize(dY, ROW) [M,N],  Wq  = quantize(W,  COL) [K,N]  ->  dX [M,K]
- *   wgrad: dYq = quantize(dY, COL) [N,M],  Xq  = quantize(X,  COL) [K,M]  ->  dW [N,K]   */
+ *   wgrad: dYq = quantize(dY, COL) [N,M],  Xq  = quantize(X,  COL) [K,M]  ->  dW [N,K]
+ *
+ * Every output element sums its products in one fixed order, whichever kernel and workgroup tile
+ * the launcher picks for the shape.  The matrix-core kernel has two tiles (256 x 256 and 256 x 128
+ * outputs per workgroup); the environment variable SNIP_GEMM_TILE=big|wide, read at every call,
+ * fixes the tile for measurements and tests and never changes a result. */
 snip_status snip_gemm_fwd(const snip_layer_plan* plan, const snip_qtensor* xq_row,
                           const snip_qtensor* wq_row, void* y, int64_t ld_out,
                           snip_out_dtype out_dtype, void* workspace, size_t workspace_bytes,

@@ -44,11 +44,21 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
-constexpr int TM = 256, TN = 256;       // workgroup tile
 constexpr int NWAVE = 8, NT = NWAVE * 64;
-constexpr int WTM = 128, WTN = 64;      // wave tile
-constexpr int WGN = TN / WTN;           // waves along the B rows
-constexpr int MB = WTM / 32, NB = WTN / 32;
+constexpr int TNP = 256;                // rows of the B tile's scale area (a 128-row B tile leaves half of it unused)
+
+// Workgroup tile TM (A rows) x TN (B rows), split over the eight waves as (TM / WTM) x (TN / WTN) wave tiles.
+template <int TM_, int TN_, int WTM_, int WTN_> struct TileCfg {
+    static constexpr int TM = TM_, TN = TN_, WTM = WTM_, WTN = WTN_;
+    static constexpr int WGN = TN / WTN;                   // waves along the B rows
+    static constexpr int MB = WTM / 32, NB = WTN / 32;     // 32 x 32 MFMA blocks of a wave tile
+    static_assert(TM == 256 && (TN == 256 || TN == 128), "copy shares and scale areas are laid out for these tiles");
+    static_assert((TM / WTM) * (TN / WTN) == NWAVE, "eight waves");
+};
+// 256 x 256, 2 x 4 waves of 128 x 64: the largest tile the register file allows (fewest operand bytes per FLOP).
+using TileBig = TileCfg<256, 256, 128, 64>;
+// 256 x 128, 4 x 2 waves of 64 x 64: twice as many tiles for outputs that would leave compute units without one.
+using TileWide = TileCfg<256, 128, 64, 64>;
 
 // Global -> LDS copy issued by the load unit: lane i's 16 (or 4) bytes land at lds + 16*i (4*i); `lds` is
 // wave-uniform and travels in M0.  Written as inline assembly on purpose: the compiler then keeps no
@@ -71,7 +81,8 @@ __device__ __forceinline__ void glds4(const uint8_t* base, unsigned lane_off, un
 // s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding: vmcnt[3:0], expcnt[6:4], lgkmcnt[11:8], vmcnt[5:4] in [15:14])
 #define SNIP_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
 
-template <int FA, int FB> struct FCfg {
+template <int FA, int FB, class T> struct FCfg {
+    static constexpr int TM = T::TM, TN = T::TN;
     static constexpr bool BOTH4 = FA == kFP4 && FB == kFP4;
     static constexpr int KE = BOTH4 ? 256 : 128;                 // contraction elements per stage
     static constexpr int SBA = FA == kFP8 ? KE : KE / 2;         // code bytes per row per stage (128, or 64 for FP4 next to FP8)
@@ -80,7 +91,7 @@ template <int FA, int FB> struct FCfg {
     static constexpr int NG = KE / 128;                          // scale dwords (groups of 4 blocks) per row per stage
     static constexpr int NST = 2;                                // stage buffers
     static constexpr int A_BYTES = TM * SBA, B_BYTES = TN * SBB;
-    static constexpr int S_BYTES = (TM + TN) * NG * 4;           // scale dwords of one stage
+    static constexpr int S_BYTES = (TM + TNP) * NG * 4;          // scale dwords of one stage
     static constexpr int SLOT = A_BYTES + B_BYTES + S_BYTES;
     // Stage buffer 0 sits at the start of the LDS array and stage buffer 1 at its end; the result staging area is
     // the first or the last EPI_BYTES of the array, i.e. it covers the buffer of the tile's last stage (plus the
@@ -152,7 +163,7 @@ __device__ __forceinline__ void tile_of(int u, int nblk, int tiles_i, int tiles_
     tj = rem / rows_in_band;
 }
 
-template <int FA, int FB, bool OUT_F32>
+template <int FA, int FB, bool OUT_F32, class T>
 __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict__ a_codes,
                                                        const uint8_t* __restrict__ a_g4,
                                                        const uint8_t* __restrict__ b_codes,
@@ -161,7 +172,8 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
                                                        int tiles_i, int tiles_j, float* __restrict__ norm_partials,
                                                        int stream_out)
 {
-    using C = FCfg<FA, FB>;
+    using C = FCfg<FA, FB, T>;
+    constexpr int TM = T::TM, TN = T::TN, WTM = T::WTM, WTN = T::WTN, WGN = T::WGN, MB = T::MB, NB = T::NB;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[C::LDS_BYTES];
     // stage buffer layout: [A codes][B codes][A scale dwords: group-major, 256 rows][B scale dwords]
 
@@ -208,7 +220,9 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
 #pragma unroll
         for (int j = 0; j < C::LS; ++j) {
             const int q = wave * C::LS + j;
-            const int opnd = q / (4 * C::NG), grp = (q % (4 * C::NG)) / 4, quarter = q % 4;
+            const int opnd = q / (4 * C::NG), grp = (q % (4 * C::NG)) / 4;
+            int quarter = q % 4;
+            if (opnd == 1 && quarter * 64 >= TN) quarter -= TN / 64;      // a 128-row B tile: fetch its rows again (unused copy)
             const int64_t pitch = opnd == 0 ? a_pitch : b_pitch;
             sbase[j] = (opnd == 0 ? a_g4 : b_g4) + ((int64_t)grp * pitch + (opnd == 0 ? i0 : j0) + quarter * 64) * 4;
             sstep[j] = (int64_t)C::NG * pitch * 4;
@@ -276,7 +290,7 @@ __global__ __launch_bounds__(NT) void gemm_fast_kernel(const uint8_t* __restrict
 #pragma unroll
         for (int m = 0; m < MB; ++m) sa[m] = *reinterpret_cast<const unsigned*>(base + sca_off + q * TM * 4 + m * 128) >> (8 * g);
 #pragma unroll
-        for (int n = 0; n < NB; ++n) sb[n] = *reinterpret_cast<const unsigned*>(base + scb_off + q * TN * 4 + n * 128) >> (8 * g);
+        for (int n = 0; n < NB; ++n) sb[n] = *reinterpret_cast<const unsigned*>(base + scb_off + q * TNP * 4 + n * 128) >> (8 * g);
 #pragma unroll
         for (int k = 0; k < KP; ++k) {
 #pragma unroll
@@ -546,10 +560,30 @@ int compute_units()
     return cached[dev];
 }
 
-template <int FA, int FB>
+// Which tile serves an I x J output best: the estimate is rounds of tiles over the compute units times the time of a
+// tile; a 256 x 128 tile takes 0.6 of the time of a 256 x 256 one (half the MFMAs, three quarters of the operand bytes).
+// The wide tile wins where the big one would leave compute units without a tile, or a last round nearly empty.
+bool prefer_wide_tile(const GemmArgs& a)
+{
+    // SNIP_GEMM_TILE=big|wide in the environment fixes the tile (read at every call, so a test can cover both tiles
+    // on every shape); anything else leaves the choice to the estimate below
+    if (const char* e = getenv("SNIP_GEMM_TILE")) {
+        if (e[0] == 'w') return true;
+        if (e[0] == 'b') return false;
+    }
+    // A 256 x 128 tile costs about 0.8 of a 256 x 256 one (measured on one-round launches: per flop it reads more
+    // of the LDS and stores as often), so it only pays while it fills compute units the larger tile would leave
+    // idle, i.e. while it does not add a round of tiles.
+    const int64_t ncu = compute_units();
+    const int64_t big = ((a.I + 255) / 256) * ((a.J + 255) / 256), wide = ((a.I + 255) / 256) * ((a.J + 127) / 128);
+    const double t_big = (double)((big + ncu - 1) / ncu), t_wide = 0.8 * (double)((wide + ncu - 1) / ncu);
+    return t_wide < t_big;
+}
+
+template <int FA, int FB, class T>
 hipError_t launch_fast_t(const GemmArgs& a, hipStream_t s)
 {
-    const int ti = (int)((a.I + TM - 1) / TM), tj = (int)((a.J + TN - 1) / TN);
+    const int ti = (int)((a.I + T::TM - 1) / T::TM), tj = (int)((a.J + T::TN - 1) / T::TN);
     // one workgroup per compute unit (the LDS array admits no second one), each walking its share of the tiles
     const int ncu = compute_units();
     const dim3 grid((unsigned)(ti * tj < ncu ? ti * tj : ncu)), block(NT);
@@ -559,12 +593,21 @@ hipError_t launch_fast_t(const GemmArgs& a, hipStream_t s)
                          (double)a.I * a.J * (a.out_fp32 ? 4.0 : 2.0);
     int stream_out = bytes > 200e6;
     if (a.out_fp32)
-        hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, true>), grid, block, 0, s, a.a_codes, a.a_scales_g4, a.b_codes, a.b_scales_g4,
+        hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, true, T>), grid, block, 0, s, a.a_codes, a.a_scales_g4, a.b_codes, a.b_scales_g4,
                            (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj, a.norm_partials, stream_out);
     else
-        hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, false>), grid, block, 0, s, a.a_codes, a.a_scales_g4, a.b_codes, a.b_scales_g4,
+        hipLaunchKernelGGL((gemm_fast_kernel<FA, FB, false, T>), grid, block, 0, s, a.a_codes, a.a_scales_g4, a.b_codes, a.b_scales_g4,
                            (int)a.I, (int)a.J, (int)a.R, a.c, a.ldc, ti, tj, a.norm_partials, stream_out);
     return hipGetLastError();
+}
+
+template <class T>
+hipError_t launch_fast_tile(const GemmArgs& a, hipStream_t s)
+{
+    if (a.fmt_a == kFP8 && a.fmt_b == kFP8) return launch_fast_t<kFP8, kFP8, T>(a, s);
+    if (a.fmt_a == kFP8 && a.fmt_b == kFP4) return launch_fast_t<kFP8, kFP4, T>(a, s);
+    if (a.fmt_a == kFP4 && a.fmt_b == kFP8) return launch_fast_t<kFP4, kFP8, T>(a, s);
+    return launch_fast_t<kFP4, kFP4, T>(a, s);
 }
 
 }  // namespace
@@ -576,14 +619,14 @@ bool gemm_fast_eligible(const GemmArgs& a)
     return a.a_scales_g4 && a.b_scales_g4 && a.R % ke == 0 && a.R >= 2 * ke && a.I > 128 && a.J > 128;
 }
 
-int64_t gemm_fast_partials(const GemmArgs& a) { return ((a.I + TM - 1) / TM) * ((a.J + TN - 1) / TN); }
+int64_t gemm_fast_partials(const GemmArgs& a)
+{
+    return ((a.I + 255) / 256) * (prefer_wide_tile(a) ? (a.J + 127) / 128 : (a.J + 255) / 256);
+}
 
 hipError_t launch_gemm_fast(const GemmArgs& a, hipStream_t s)
 {
-    if (a.fmt_a == kFP8 && a.fmt_b == kFP8) return launch_fast_t<kFP8, kFP8>(a, s);
-    if (a.fmt_a == kFP8 && a.fmt_b == kFP4) return launch_fast_t<kFP8, kFP4>(a, s);
-    if (a.fmt_a == kFP4 && a.fmt_b == kFP8) return launch_fast_t<kFP4, kFP8>(a, s);
-    return launch_fast_t<kFP4, kFP4>(a, s);
+    return prefer_wide_tile(a) ? launch_fast_tile<TileWide>(a, s) : launch_fast_tile<TileBig>(a, s);
 }
 
 }  // namespace snip

@@ -1022,16 +1022,9 @@ size_t workspace_bytes(int64_t rows, int64_t cols)
 // Workgroups for `units` equal work units that waves take in turn: as many waves as give every wave the
 // same number of units (the last one possibly fewer), at most kStreamWaves.  11008 units on 8192 waves would
 // leave three quarters of the device idle during the second turn; 5504 waves take two units each.
-static int exp_waves()
-{
-    static int v = -1;
-    if (v < 0) { const char* e = getenv("SNIP_EXP_WAVES"); v = e ? atoi(e) : kStreamWaves; }
-    return v;
-}
 static int balanced_blocks(int64_t units)
 {
     if (units <= 0) return 1;
-    const int64_t kStreamWaves = exp_waves();
     const int64_t per_wave = (units + kStreamWaves - 1) / kStreamWaves;
     const int64_t waves = (units + per_wave - 1) / per_wave;
     return (int)((waves + kWavesPerBlock - 1) / kWavesPerBlock);

@@ -10,3 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a gfx950 GPU and the built HIP library")
+
+
+@pytest.fixture(params=["big", "wide"])
+def gemm_tile(request, monkeypatch):
+    """Runs a GEMM test once per workgroup tile of the MFMA kernel (256 x 256 and 256 x 128): the library reads
+    SNIP_GEMM_TILE at every GEMM call, so both tiles see every shape, whatever the launcher would pick itself."""
+    monkeypatch.setenv("SNIP_GEMM_TILE", request.param)
+    return request.param

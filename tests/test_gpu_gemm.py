@@ -8,7 +8,7 @@ from paper_2602_01410_amd import workloads as wl
 
 from gpu_util import host, host_bf16_as_f64, rel_fro, require_gpu, to_dev
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("gemm_tile")]
 TOL_BF16 = 2e-3      # relative Frobenius error, bf16 output (one RNE to bf16 costs ~1.7e-3)
 TOL_F32 = 1e-4       # fp32 output: the matrix core sums the 64 products of one instruction with a
                      # shared alignment, not as IEEE fp32 adds; measured 1e-5 .. 3e-5
@@ -162,3 +162,32 @@ def test_error_codes():
     with pytest.raises(snip.SnipError) as e:
         snip.snip_quantize(x, snip.FP8, snip.ROW, out=snip.alloc_qtensor(32, 64, snip.FP8))
     assert e.value.status == 2
+
+
+@pytest.mark.parametrize("fa,fb", [(0, 0), (1, 1), (0, 1)])
+def test_tiles_agree_bit_for_bit_and_the_launcher_takes_one_of_them(fa, fb, monkeypatch):
+    """Every output element sums the same products in the same order under either workgroup tile, so the two tiles
+    and the launcher's own pick give identical bits: at a shape where the pick is the narrower tile (its tiles fit
+    one round of workgroups) and at one where it is the larger."""
+    snip = require_gpu()
+    rng = np.random.default_rng(4242)
+    for (I, J, R) in ((700, 1300, 512), (4200, 4300, 256)):
+        a_bits = wl.f32_to_bf16_bits(rng.standard_normal((I, R)).astype(np.float32))
+        b_bits = wl.f32_to_bf16_bits(rng.standard_normal((J, R)).astype(np.float32))
+        aq, bq = snip.snip_quantize(to_dev(a_bits), fa, snip.ROW), snip.snip_quantize(to_dev(b_bits), fb, snip.ROW)
+        plan = snip.make_plan((fa, fb, 0, 0, 0, 0))
+        outs = {}
+        for tile in ("big", "wide", None):
+            if tile is None:
+                monkeypatch.delenv("SNIP_GEMM_TILE", raising=False)
+            else:
+                monkeypatch.setenv("SNIP_GEMM_TILE", tile)
+            y, nrm = snip.snip_gemm_fwd_norm(plan, aq, bq, out_dtype=1)
+            torch.cuda.synchronize()
+            outs[tile] = (host(y), host(nrm))
+        assert np.array_equal(outs["big"][0], outs["wide"][0])
+        assert np.array_equal(outs[None][0], outs["big"][0])
+        want = oracle.gemm_fwd(oracle.fake_quant(a_bits, fa, oracle.ROW), oracle.fake_quant(b_bits, fb, oracle.ROW))
+        assert rel_fro(outs[None][0].astype(np.float64), want) <= TOL_F32
+        for t in outs:
+            assert float(outs[t][1][0]) == pytest.approx(float((outs[t][0].astype(np.float64) ** 2).sum()), rel=5e-6)

@@ -15,7 +15,7 @@ from paper_2602_01410_amd import workloads as wl
 
 from gpu_util import host, host_bf16_as_f64, require_gpu, to_dev
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("gemm_tile")]
 TOL_NORM = 1e-4
 
 

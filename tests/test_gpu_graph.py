@@ -9,7 +9,7 @@ from paper_2602_01410_amd import workloads as wl
 
 from gpu_util import require_gpu, to_dev
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("gemm_tile")]
 
 
 def test_graph_replay_matches_eager():

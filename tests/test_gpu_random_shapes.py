@@ -97,6 +97,7 @@ def test_quantize_random_shapes(case):
     np.testing.assert_allclose(host(bc), oracle.stats(bits, oracle.COL, rule), rtol=1e-5)
 
 
+@pytest.mark.usefixtures("gemm_tile")
 @pytest.mark.parametrize("case", range(16))
 def test_gemm_random_shapes(case):
     """Odd cases take extents that admit the large-tile kernel (both output extents above 128, contraction a
