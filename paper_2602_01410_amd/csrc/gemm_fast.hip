@@ -23,12 +23,16 @@
 //   start-up latency is paid once per workgroup, not once per tile.  The result tile is staged in the other
 //   stage buffer (the one the last stage was read from), 64 KB at a time.
 //
-// Measured with s_memtime stamps around every phase (FP4 x FP4, 256 contraction elements per
-// stage): an MFMA phase takes 505 ticks (16 MFMAs x 32), a read phase 390 (one wave issues a
-// ds_read_b128 about every 29 ticks whatever the other waves do), a barrier 40-60.  Under load
-// the ticks arrive at 1.1-1.45 G/s on random codes and 1.8 G/s on all-zero codes (the shader clock shown
-// by the system tools falls from 2.4 to 1.85-1.9 GHz likewise): the kernel is limited by power, so
-// removing idle cycles gains less than proportionally.
+// What bounds it (hardware counters and variants of this kernel with one part removed, 16384 x 4096 x 4096 and
+// 4096 x 4096 x 16384 on Gaussian data): the matrix cores are busy for 0.62-0.64 of the compute units' busy cycles
+// and the shader clock (GRBM_GUI_ACTIVE over the launch duration) is 1.83 GHz (FP4) to 1.95 GHz (FP8) instead of 2.4;
+// a loop of nothing but MFMAs on random operands runs at 1.64 / 2.03 GHz.  LDS is active a third of the time with
+// 2 % bank-conflict cycles.  Leaving out the workgroup barriers changes nothing.  Leaving out the global -> LDS
+// copies gains 20 % on random codes but 7 % on all-zero codes, half of the copies 8.5 %, and copies that always
+// hit one L2-resident stage 5 %: what the copies cost is mostly clock (the chip slows down as more random bytes
+// move through a compute unit), not latency and not misses.  The result stores cost 10 % at contraction extent
+// 4096: all workgroups finish a tile together, 32 MB per round, and the next tile's copies queue behind them in
+// the wave's memory counter.
 //
 // See gemm.hip for the register layout of v_mfma_scale_f32_32x32x64_f8f6f4.
 #include "snip_internal.h"

@@ -178,8 +178,52 @@ int hbm_sweep()
     return 0;
 }
 
+
+// LDS read bandwidth: every lane of NW waves reads W-byte words, conflict-free (consecutive lanes, consecutive
+// words), from a 64 KB array, UNR reads in flight per lane.
+template <int W>
+__global__ __launch_bounds__(512) void k_lds_read(int iters, uint32_t* out)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[65536];
+    for (int i = threadIdx.x; i < 65536 / 4; i += blockDim.x) ((uint32_t*)lds)[i] = i;
+    __syncthreads();
+    uint32_t acc = 0;
+    unsigned off = threadIdx.x * W;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const unsigned a = (off + u * 8192) & 65535u;
+            if (W == 16) { const uint4 v = *(const uint4*)(lds + a); acc ^= v.x ^ v.y ^ v.z ^ v.w; }
+            else if (W == 8) { const uint2 v = *(const uint2*)(lds + a); acc ^= v.x ^ v.y; }
+            else { acc ^= *(const uint32_t*)(lds + a); }
+        }
+        off += 1024;
+    }
+    if (acc == 0x12345678u) out[blockIdx.x] = acc;
+}
+
+static int lds_bench()
+{
+    uint32_t* out; CK(hipMalloc(&out, 4096 * 4));
+    const int iters = 4000;
+    printf("{");
+    for (int nw : {4, 8}) {
+        float ms;
+        const double n = 1024.0 * nw * 64 * iters * 8;
+        ms = time_ms([&] { k_lds_read<16><<<1024, nw * 64>>>(iters, out); }, 3);
+        printf("\"lds_read_b128_%dwaves_tbps\": %.1f, ", nw, n * 16 / ms / 1e9);
+        ms = time_ms([&] { k_lds_read<8><<<1024, nw * 64>>>(iters, out); }, 3);
+        printf("\"lds_read_b64_%dwaves_tbps\": %.1f, ", nw, n * 8 / ms / 1e9);
+        ms = time_ms([&] { k_lds_read<4><<<1024, nw * 64>>>(iters, out); }, 3);
+        printf("\"lds_read_b32_%dwaves_tbps\": %.1f%s", nw, n * 4 / ms / 1e9, nw == 8 ? "" : ", ");
+    }
+    printf("}\n");
+    return 0;
+}
+
 int main(int argc, char** argv)
 {
+    if (argc > 1 && std::string(argv[1]) == "lds") return lds_bench();
     if (argc > 1 && std::string(argv[1]) == "hbm-sweep") return hbm_sweep();
     int* rnd; CK(hipMalloc(&rnd, 16384 * 4));
     static int h[16384]; srand(1); for (int i = 0; i < 16384; ++i) h[i] = rand() ^ (rand() << 16);
