@@ -191,3 +191,24 @@ def test_tiles_agree_bit_for_bit_and_the_launcher_takes_one_of_them(fa, fb, monk
         assert rel_fro(outs[None][0].astype(np.float64), want) <= TOL_F32
         for t in outs:
             assert float(outs[t][1][0]) == pytest.approx(float((outs[t][0].astype(np.float64) ** 2).sum()), rel=5e-6)
+
+
+@pytest.mark.parametrize("fmt", [0, 1])
+def test_persistent_launch_is_deterministic(fmt):
+    """More tiles than compute units (workgroups walk several tiles, the next tile's operands are fetched while
+    the current one finishes): two launches give the same bits, with and without the output norm."""
+    snip = require_gpu()
+    rng = np.random.default_rng(77 + fmt)
+    I, J, R = 4700, 4500, 512                # 19 x 18 (or 19 x 36) tiles on 256 compute units, ragged edges
+    a_bits = wl.f32_to_bf16_bits(rng.standard_normal((I, R)).astype(np.float32))
+    b_bits = wl.f32_to_bf16_bits(rng.standard_normal((J, R)).astype(np.float32))
+    aq, bq = snip.snip_quantize(to_dev(a_bits), fmt, snip.ROW), snip.snip_quantize(to_dev(b_bits), fmt, snip.ROW)
+    plan = snip.make_plan((fmt, fmt, 0, 0, 0, 0))
+    y1 = snip.snip_gemm_fwd(plan, aq, bq)
+    y2, n2 = snip.snip_gemm_fwd_norm(plan, aq, bq)
+    y3, n3 = snip.snip_gemm_fwd_norm(plan, aq, bq)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2) and torch.equal(y2, y3) and torch.equal(n2, n3)
+    rows = rng.choice(I, 64, replace=False)
+    want = oracle.gemm_fwd(oracle.fake_quant(a_bits[rows], fmt, oracle.ROW), oracle.fake_quant(b_bits, fmt, oracle.ROW))
+    assert rel_fro(host_bf16_as_f64(y1[torch.as_tensor(rows, device="cuda")]), want) <= TOL_BF16
