@@ -2,7 +2,8 @@
 // (scales_g4) and the contraction extent is a multiple of the stage length.
 //
 //   workgroup tile 256 x 256, 8 waves (2 x 4), wave tile 128 (A rows) x 64 (B rows), fp32
-//   accumulators in registers (128 per lane).
+//   accumulators in registers (128 per lane); for outputs that would leave compute units without a
+//   tile, 256 x 128 with 4 x 2 waves of 64 x 64 (same code, other template argument).
 //   A pipeline stage is 128 code bytes of every tile row for an FP8 operand and for FP4 x FP4
 //   (256 contraction elements there), so every 128-byte line that is fetched is used whole.
 //   Codes and scale dwords go global -> LDS through the load unit (global_load_lds), never through

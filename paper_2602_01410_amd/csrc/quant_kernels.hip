@@ -15,7 +15,6 @@
 //             (exact in fp32) is squared and summed in fp32 per lane, then per wave, and the
 //             per-wave partials are summed in double by a single-block kernel in fixed order.
 #include "snip_internal.h"
-#include <cstdlib>
 
 namespace snip {
 namespace {

@@ -114,7 +114,7 @@ hipError_t launch_stats(const StatsArgs& a, hipStream_t s);
 // (a.axis and a.per_line are ignored)
 hipError_t launch_stats_both(const StatsArgs& a, double* out_col, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
-bool gemm_fast_eligible(const GemmArgs& a);          // 256x256-tile kernel (gemm_fast.hip)
+bool gemm_fast_eligible(const GemmArgs& a);          // persistent large-tile kernel (gemm_fast.hip)
 hipError_t launch_gemm_fast(const GemmArgs& a, hipStream_t s);
 int64_t gemm_fast_partials(const GemmArgs& a);         // partials launch_gemm_fast writes
 
