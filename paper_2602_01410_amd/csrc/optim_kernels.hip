@@ -12,6 +12,9 @@
 namespace snip {
 namespace {
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
 __device__ __forceinline__ float sens_term(float m, float v, float g, float c1, float c2, float eps)
 {
     const float root = __fsqrt_rn(v);
@@ -35,15 +38,16 @@ __global__ __launch_bounds__(256) void adamw_sens_kernel(const float* __restrict
     const int64_t n4 = n / 4;
     float acc = 0.f;
     for (int64_t q = tid; q < n4; q += nthreads) {
-        const float4 mm = reinterpret_cast<const float4*>(m)[q];
-        const float4 vv = reinterpret_cast<const float4*>(v)[q];
-        float4 gg;
+        // streaming (non-temporal) loads: nothing is read twice and the three arrays exceed every cache
+        const v4f mm = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(m) + q);
+        const v4f vv = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(v) + q);
+        v4f gg;
         if (G_BF16) {
-            const uint2 w = reinterpret_cast<const uint2*>(g)[q];
-            gg = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
-                             __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
+            const v2u w = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(g) + q);
+            gg = v4f{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
+                     __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u)};
         } else {
-            gg = reinterpret_cast<const float4*>(g)[q];
+            gg = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g) + q);
         }
         acc += sens_term(mm.x, vv.x, gg.x, c1, c2, eps);
         acc += sens_term(mm.y, vv.y, gg.y, c1, c2, eps);

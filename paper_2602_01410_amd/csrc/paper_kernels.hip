@@ -21,6 +21,15 @@ namespace {
 typedef short short2_t __attribute__((ext_vector_type(2)));
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+// Streaming (non-temporal) loads for sources that are read once.
+__device__ __forceinline__ uint4 ld16_stream(const void* p)
+{
+    const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ unsigned ld4_stream(const void* p) { return __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(p)); }
 
 constexpr int kGroup = 128;              // scaling-group extent along the blocked dimension
 constexpr int kSeg = 512;                // elements of a row one wave handles per load
@@ -204,7 +213,7 @@ __global__ __launch_bounds__(256) void paper_row_kernel(const uint16_t* __restri
             const int row = rg * kUnroll + j;
             act[j] = row < rows && col < cols;
             v[j] = make_uint4(0, 0, 0, 0);
-            if (act[j]) v[j] = *reinterpret_cast<const uint4*>(x + (int64_t)row * ld + col);
+            if (act[j]) v[j] = ld16_stream(x + (int64_t)row * ld + col);
         }
 #pragma unroll
         for (int j = 0; j < kUnroll; ++j) {
@@ -355,7 +364,7 @@ __global__ __launch_bounds__(256) void paper_col_kernel(const uint16_t* __restri
 #pragma unroll
         for (int k = 0; k < 4; ++k)
 #pragma unroll
-            for (int i = 0; i < 32; ++i) v[k][i] = *reinterpret_cast<const unsigned*>(base + (int64_t)(k * 32 + i) * ld);
+            for (int i = 0; i < 32; ++i) v[k][i] = ld4_stream(base + (int64_t)(k * 32 + i) * ld);
         if ((cg + 1) * kColsPerWave > cols) {
 #pragma unroll
             for (int k = 0; k < 4; ++k)
