@@ -164,7 +164,11 @@ typedef enum { SNIP_STATS_CHOSEN_FORMAT = 0, SNIP_STATS_BOTH_FORMATS = 1 } snip_
  *             snip_quant_error_stats_both delivers, out of the same pass: the complete Step-1
  *             record of a tensor (Sec. 3.1; the ILP needs the error of the option not in use,
  *             Sec. 4.2) together with its two quantized orientations from one read.  Ignored
- *             without statistics outputs. */
+ *             without statistics outputs.
+ * Small tensors are worked on by one workgroup per 128-column unit, large ones by one wave per unit;
+ * the environment variable SNIP_QUANT_BOTH_UNIT=wave|workgroup, read at every call, fixes the choice
+ * for tests and measurements (codes and scales do not depend on it; the statistics are summed in
+ * another fixed order). */
 snip_status snip_quantize_both(const void* x, int64_t rows, int64_t cols, int64_t ld,
                                snip_scale_rule rule, const snip_qtensor* out_row,
                                const snip_qtensor* out_col, snip_stats* stats_row,

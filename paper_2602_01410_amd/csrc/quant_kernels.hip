@@ -15,6 +15,7 @@
 //             (exact in fp32) is squared and summed in fp32 per lane, then per wave, and the
 //             per-wave partials are summed in double by a single-block kernel in fixed order.
 #include "snip_internal.h"
+#include <cstdlib>
 
 namespace snip {
 namespace {
@@ -584,7 +585,10 @@ __device__ __forceinline__ void other_format_error(const unsigned* w, unsigned a
     }
 }
 
-template <int FMT_R, int FMT_C, int RULE, int STATS>      // STATS: 0 none, 1 the chosen formats' errors, 2 both formats' errors
+// COOP: the four waves of a workgroup share one unit (wave w takes its tiles w, w + 4, ...) and one staging area,
+// for tensors with too few units to give every SIMD a wave: a unit's tiles are then worked on side by side instead
+// of one after the other.  Same bytes out.
+template <int FMT_R, int FMT_C, int RULE, int STATS, bool COOP = false>      // STATS: 0 none, 1 the chosen formats' errors, 2 both formats' errors
 __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restrict__ x, int rows, int cols, int64_t ld,
                                                          uint8_t* __restrict__ codes_r, uint8_t* __restrict__ scales_r,
                                                          uint8_t* __restrict__ g4_r, int64_t kpitch_r,
@@ -598,21 +602,25 @@ __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restr
     // Without the statistics the loads of the next tile are issued before the current one is worked on (two sets
     // of 64 registers); with them the wave is bound by its arithmetic and the plain loop is faster.
     constexpr bool PREFETCH = STATS == 0;
-    __shared__ __attribute__((aligned(16))) uint8_t stage[kWavesPerBlock][kColsPerWave * ROWB];
+    __shared__ __attribute__((aligned(16))) uint8_t stage[COOP ? 1 : kWavesPerBlock][kColsPerWave * ROWB];
+    __shared__ __attribute__((aligned(4))) uint8_t scale_stage[COOP ? RBU * kColsPerWave : 4];   // COOP: scale byte of (tile, column)
     const int lane = threadIdx.x & 63;
-    uint8_t* const reg = stage[threadIdx.x >> 6];
-    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint8_t* const reg = stage[COOP ? 0 : wib];
+    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + wib);
     const int nwaves = gridDim.x * kWavesPerBlock;
     const int ncg = (cols + kColsPerWave - 1) / kColsPerWave;
     const int nrb = rows / kBlock;
     const int nru = (nrb + RBU - 1) / RBU;
     const int units = ncg * nru;
     const int nblk = cols / kBlock;                       // blocks per row of the row-direction output
+    constexpr int KSTEP = COOP ? kWavesPerBlock : 1;      // distance between the tiles one wave takes
+    const int k_first = COOP ? wib : 0;
     const int64_t out_row_bytes = FMT_C == kFP8 ? rows : rows / 2;
     const uint2 no_seed = make_uint2(0, 0);
     float s0 = 0.f, se_c = 0.f, se_r = 0.f;
     float so_c = 0.f, so_r = 0.f;                         // STATS == 2: error sums of the format not chosen
-    for (int u = wave; u < units; u += nwaves) {
+    for (int u = COOP ? (int)blockIdx.x : wave; u < units; u += COOP ? (int)gridDim.x : nwaves) {
         const int ru = u / ncg, cg = u - ru * ncg;
         const int c = cg * kColsPerWave + lane * 2;
         const bool act = c < cols;
@@ -626,6 +634,22 @@ __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restr
         // Loads carry no condition (a lane past the last column reads column 0 of the same rows instead and is
         // zeroed afterwards, under a wave-uniform test), so that all 40 of a tile stay in flight together.
         const bool ragged = (cg + 1) * kColsPerWave > cols;
+        // Four row blocks done (the last group of a tensor may hold fewer: blocks 0 .. last): their scale bytes of a
+        // column are one dword of the row-major array (when the row length allows it) and exactly one dword of the
+        // grouped copy.
+        auto store_col_scales = [&](int rbh, int last, unsigned lo, unsigned hi) {
+            if (act) {
+                uint8_t* s_lo = scales_c + (int64_t)c * nrb + rbh;
+                if ((nrb & 3) == 0) {
+                    *reinterpret_cast<unsigned*>(s_lo) = lo;
+                    *reinterpret_cast<unsigned*>(s_lo + nrb) = hi;
+                } else {
+                    for (int i = 0; i <= last; ++i) { s_lo[i] = (uint8_t)(lo >> (8 * i)); s_lo[nrb + i] = (uint8_t)(hi >> (8 * i)); }
+                }
+                if (g4_c)
+                    *reinterpret_cast<uint2*>(g4_c + ((int64_t)(rbh / kRowBlocksPerUnit) * kpitch_c + c) * 4) = make_uint2(lo, hi);
+            }
+        };
         auto fetch_row = [&](int k, uint4 (&rv)[8]) {
             const uint16_t* pr = x + (int64_t)((rb0 + k) * kBlock + (lane >> 4)) * ld + (ract ? rcol : 0);
 #pragma unroll
@@ -647,28 +671,20 @@ __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restr
             pair_col_block(cv, b);
             const unsigned y0 = quant_one_column<FMT_C, RULE, STATS != 0, false>(b.lo, b.am_lo, reg + (2 * lane) * ROWB, k, swz_lo, s0, se_c, 0, no_seed);
             const unsigned y1 = quant_one_column<FMT_C, RULE, STATS != 0, false>(b.hi, b.am_hi, reg + (2 * lane + 1) * ROWB, k, swz_lo, s0, se_c, 0, no_seed);
-            g4_lo |= y0 << (8 * (k & 3));
-            g4_hi |= y1 << (8 * (k & 3));
             if (STATS == 2) {
                 other_format_error<1 - FMT_C, RULE>(b.lo, b.am_lo, so_c);
                 other_format_error<1 - FMT_C, RULE>(b.hi, b.am_hi, so_c);
             }
-            if ((k & 3) == 3 || k == nb - 1) {
-                // four row blocks done: their scale bytes of a column are one dword of the row-major array (when
-                // the row length allows it) and exactly one dword of the grouped copy
-                const int rbh = rb0 + (k & ~3);
-                if (act) {
-                    uint8_t* s_lo = scales_c + (int64_t)c * nrb + rbh;
-                    if ((nrb & 3) == 0) {
-                        *reinterpret_cast<unsigned*>(s_lo) = g4_lo;
-                        *reinterpret_cast<unsigned*>(s_lo + nrb) = g4_hi;
-                    } else {
-                        for (int i = 0; i <= (k & 3); ++i) { s_lo[i] = (uint8_t)(g4_lo >> (8 * i)); s_lo[nrb + i] = (uint8_t)(g4_hi >> (8 * i)); }
-                    }
-                    if (g4_c)
-                        *reinterpret_cast<uint2*>(g4_c + ((int64_t)(rbh / kRowBlocksPerUnit) * kpitch_c + c) * 4) = make_uint2(g4_lo, g4_hi);
+            if (COOP) {
+                // the four tiles of a dword belong to four waves: the bytes meet in LDS after the unit's barrier
+                *reinterpret_cast<uint16_t*>(scale_stage + k * kColsPerWave + 2 * lane) = (uint16_t)(y0 | (y1 << 8));
+            } else {
+                g4_lo |= y0 << (8 * (k & 3));
+                g4_hi |= y1 << (8 * (k & 3));
+                if ((k & 3) == 3 || k == nb - 1) {
+                    store_col_scales(rb0 + (k & ~3), k & 3, g4_lo, g4_hi);
+                    g4_lo = 0; g4_hi = 0;
                 }
-                g4_lo = 0; g4_hi = 0;
             }
             // ---- row direction
             const int row0 = (rb0 + k) * kBlock + (lane >> 4);
@@ -720,25 +736,38 @@ __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restr
         if (PREFETCH) {
             unsigned cv0[32], cv1[32];
             uint4 rv0[8], rv1[8];
-            fetch(0, cv0, rv0);
-            for (int k = 0; k < nb; k += 2) {
-                if (k + 1 < nb) fetch(k + 1, cv1, rv1);
+            if (k_first < nb) fetch(k_first, cv0, rv0);
+            for (int k = k_first; k < nb; k += 2 * KSTEP) {
+                if (k + KSTEP < nb) fetch(k + KSTEP, cv1, rv1);
                 work(k, cv0, rv0);
-                if (k + 1 < nb) {
-                    if (k + 2 < nb) fetch(k + 2, cv0, rv0);
-                    work(k + 1, cv1, rv1);
+                if (k + KSTEP < nb) {
+                    if (k + 2 * KSTEP < nb) fetch(k + 2 * KSTEP, cv0, rv0);
+                    work(k + KSTEP, cv1, rv1);
                 }
             }
         } else {
-            for (int k = 0; k < nb; ++k) {
+            for (int k = k_first; k < nb; k += KSTEP) {
                 unsigned cv[32];
                 uint4 rv[8];
                 fetch(k, cv, rv);
                 work(k, cv, rv);
             }
         }
+        if (COOP) {
+            __syncthreads();                                   // all tiles of the unit are staged
+            for (int g = wib; 4 * g < nb; g += kWavesPerBlock) {
+                const int last = min(3, nb - 1 - 4 * g);
+                unsigned lo = 0, hi = 0;
+                for (int i = 0; i <= last; ++i) {
+                    const unsigned v = *reinterpret_cast<const uint16_t*>(scale_stage + (4 * g + i) * kColsPerWave + 2 * lane);
+                    lo |= (v & 0xFFu) << (8 * i);
+                    hi |= (v >> 8) << (8 * i);
+                }
+                store_col_scales(rb0 + 4 * g, last, lo, hi);
+            }
+        }
 #pragma unroll
-        for (int it = 0; it < kColsPerWave * CPR / 64; ++it) {
+        for (int it = k_first; it < kColsPerWave * CPR / 64; it += KSTEP) {
             const int idx = it * 64 + lane;
             const int row = idx / CPR, chunk = idx % CPR;
             const uint4 q = *reinterpret_cast<const uint4*>(reg + row * ROWB + ((chunk ^ ((row >> 1) & (CPR - 1))) * 16));
@@ -747,6 +776,7 @@ __global__ __launch_bounds__(256) void quant_both_kernel(const uint16_t* __restr
             if (cc < cols && blk < nb)
                 *reinterpret_cast<uint4*>(codes_c + (int64_t)cc * out_row_bytes + (int64_t)ru * ROWB + chunk * 16) = q;
         }
+        if (COOP) __syncthreads();                             // the staging areas go to the next unit
     }
     if (STATS) {
         s0 = wave_sum(s0);
@@ -1092,12 +1122,22 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
     return e;
 }
 
+// Up to this many units of four tiles (twice as many of eight) a tensor is quantized with one workgroup per unit
+// (COOP); the partial sums of that many workgroups fit the workspace (kStreamBlocks).
+constexpr int kCoopMaxUnits = 1024;
+static_assert(2 * kCoopMaxUnits <= kStreamBlocks, "one partial-sum slot per wave");
+
 template <int FMT_R, int FMT_C, int RULE, int STATS>
-static void launch_qb(const QuantBothArgs& a, float* partials, int blocks, hipStream_t s)
+static void launch_qb(const QuantBothArgs& a, float* partials, int blocks, bool coop, hipStream_t s)
 {
-    hipLaunchKernelGGL((quant_both_kernel<FMT_R, FMT_C, RULE, STATS>), dim3(blocks), dim3(256), 0, s,
-                       a.x, (int)a.rows, (int)a.cols, a.ld, a.codes_r, a.scales_r, a.g4_r, g4_pitch(a.rows),
-                       a.codes_c, a.scales_c, a.g4_c, g4_pitch(a.cols), partials);
+    if (coop)
+        hipLaunchKernelGGL((quant_both_kernel<FMT_R, FMT_C, RULE, STATS, true>), dim3(blocks), dim3(256), 0, s,
+                           a.x, (int)a.rows, (int)a.cols, a.ld, a.codes_r, a.scales_r, a.g4_r, g4_pitch(a.rows),
+                           a.codes_c, a.scales_c, a.g4_c, g4_pitch(a.cols), partials);
+    else
+        hipLaunchKernelGGL((quant_both_kernel<FMT_R, FMT_C, RULE, STATS, false>), dim3(blocks), dim3(256), 0, s,
+                           a.x, (int)a.rows, (int)a.cols, a.ld, a.codes_r, a.scales_r, a.g4_r, g4_pitch(a.rows),
+                           a.codes_c, a.scales_c, a.g4_c, g4_pitch(a.cols), partials);
 }
 
 hipError_t launch_quantize_both(const QuantBothArgs& a, hipStream_t s)
@@ -1113,14 +1153,23 @@ hipError_t launch_quantize_both(const QuantBothArgs& a, hipStream_t s)
     const int64_t nrb = a.rows / kBlock;
     const int rbu = a.fmt_c == kFP8 ? kRowBlocksPerUnit : 2 * kRowBlocksPerUnit;           // as in quant_both_kernel
     const int64_t units = ((a.cols + kColsPerWave - 1) / kColsPerWave) * ((nrb + rbu - 1) / rbu);
-    const int blocks = balanced_blocks(units);
+    // Few units: one workgroup per unit, its four waves sharing the unit's tiles (measured: pays up to 1024 units
+    // of four tiles and 2048 units of eight); otherwise one wave per unit.  SNIP_QUANT_BOTH_UNIT=wave|workgroup in
+    // the environment, read at every call, fixes the choice for tests and measurements (the workgroup form only up
+    // to the number of partial-sum slots).
+    bool coop = units <= (a.fmt_c == kFP8 ? kCoopMaxUnits : 2 * kCoopMaxUnits);
+    if (const char* e = getenv("SNIP_QUANT_BOTH_UNIT")) {
+        if (e[0] == 'w' && e[1] == 'a') coop = false;
+        if (e[0] == 'w' && e[1] == 'o') coop = units <= kStreamBlocks;
+    }
+    const int blocks = coop ? (int)units : balanced_blocks(units);
     const int mode = !st ? 0 : (a.both_formats ? 2 : 1);
     const int key = (a.fmt_r << 4) | (a.fmt_c << 3) | (a.rule << 2) | mode;
     switch (key) {
 #define SNIP_QB_CASE(FR, FC, RU) \
-        case ((FR) << 4) | ((FC) << 3) | ((RU) << 2) | 0: launch_qb<FR, FC, RU, 0>(a, partials, blocks, s); break; \
-        case ((FR) << 4) | ((FC) << 3) | ((RU) << 2) | 1: launch_qb<FR, FC, RU, 1>(a, partials, blocks, s); break; \
-        case ((FR) << 4) | ((FC) << 3) | ((RU) << 2) | 2: launch_qb<FR, FC, RU, 2>(a, partials, blocks, s); break;
+        case ((FR) << 4) | ((FC) << 3) | ((RU) << 2) | 0: launch_qb<FR, FC, RU, 0>(a, partials, blocks, coop, s); break; \
+        case ((FR) << 4) | ((FC) << 3) | ((RU) << 2) | 1: launch_qb<FR, FC, RU, 1>(a, partials, blocks, coop, s); break; \
+        case ((FR) << 4) | ((FC) << 3) | ((RU) << 2) | 2: launch_qb<FR, FC, RU, 2>(a, partials, blocks, coop, s); break;
         SNIP_QB_CASE(0, 0, 0) SNIP_QB_CASE(0, 0, 1) SNIP_QB_CASE(0, 1, 0) SNIP_QB_CASE(0, 1, 1)
         SNIP_QB_CASE(1, 0, 0) SNIP_QB_CASE(1, 0, 1) SNIP_QB_CASE(1, 1, 0) SNIP_QB_CASE(1, 1, 1)
 #undef SNIP_QB_CASE

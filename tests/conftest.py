@@ -18,3 +18,11 @@ def gemm_tile(request, monkeypatch):
     SNIP_GEMM_TILE at every GEMM call, so both tiles see every shape, whatever the launcher would pick itself."""
     monkeypatch.setenv("SNIP_GEMM_TILE", request.param)
     return request.param
+
+
+@pytest.fixture(params=["wave", "workgroup"])
+def quant_both_unit(request, monkeypatch):
+    """Runs a test of the one-pass two-orientation quantize once per work distribution (a wave or a workgroup per
+    128-column unit): the library reads SNIP_QUANT_BOTH_UNIT at every call."""
+    monkeypatch.setenv("SNIP_QUANT_BOTH_UNIT", request.param)
+    return request.param

@@ -10,7 +10,7 @@ from paper_2602_01410_amd import workloads as wl
 from gpu_util import host, require_gpu, to_dev
 from test_gpu_quantize import wide_range_bits
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("quant_both_unit")]
 
 FMTS = [oracle.FP8, oracle.FP4]
 RULES = [oracle.NO_OVERFLOW, oracle.FLOOR]
@@ -153,3 +153,30 @@ def test_empty_and_argument_errors():
     z = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(snip.SnipError):
         snip.snip_quantize_both(z, snip.FP8, snip.FP8, stats_row=s0)       # only one statistics output
+
+
+@pytest.mark.parametrize("shape", [(2080, 1056), (4096, 4096), (32, 160)])
+def test_wave_and_workgroup_units_write_the_same_bytes(shape, monkeypatch):
+    """The two work distributions and the launcher's own pick agree on every output byte; the statistics agree to
+    the tolerance (their partial sums are combined in another order)."""
+    snip = require_gpu()
+    rng = np.random.default_rng(5)
+    x = to_dev(wl.f32_to_bf16_bits((rng.standard_normal(shape) * np.exp(rng.normal(0, 3, (shape[0], 1)))).astype(np.float32)))
+    for fmt_r, fmt_c in ((snip.FP4, snip.FP8), (snip.FP8, snip.FP4)):
+        outs = {}
+        for unit in ("wave", "workgroup", None):
+            if unit is None:
+                monkeypatch.delenv("SNIP_QUANT_BOTH_UNIT", raising=False)
+            else:
+                monkeypatch.setenv("SNIP_QUANT_BOTH_UNIT", unit)
+            sr, sc = snip.alloc_stats(), snip.alloc_stats()
+            qr, qc = snip.snip_quantize_both(x, fmt_r, fmt_c, stats_row=sr, stats_col=sc, both_formats=True)
+            torch.cuda.synchronize()
+            outs[unit] = (qr, qc, host(sr), host(sc))
+        for unit in ("workgroup", None):
+            for i in (0, 1):
+                got, want = outs[unit][i], outs["wave"][i]
+                assert torch.equal(got.codes, want.codes) and torch.equal(got.scales, want.scales)
+                assert torch.equal(got.scales_g4[:, :got.rows], want.scales_g4[:, :want.rows])
+            for i in (2, 3):
+                np.testing.assert_allclose(outs[unit][i], outs["wave"][i], rtol=TOL)

@@ -46,6 +46,7 @@ def check_stats(st, bits, fmt, axis, rule):
     assert np.isnan(got[3 - k])
 
 
+@pytest.mark.usefixtures("quant_both_unit")
 @pytest.mark.parametrize("case", range(24))
 def test_quantize_random_shapes(case):
     snip = require_gpu()
