@@ -1122,8 +1122,8 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
     return e;
 }
 
-// Up to this many units of four tiles (twice as many of eight) a tensor is quantized with one workgroup per unit
-// (COOP); the partial sums of that many workgroups fit the workspace (kStreamBlocks).
+// Up to this many units (more in some modes, see launch_quantize_both) a tensor is quantized with one workgroup per
+// unit (COOP); the partial sums of that many workgroups fit the workspace (kStreamBlocks).
 constexpr int kCoopMaxUnits = 1024;
 static_assert(2 * kCoopMaxUnits <= kStreamBlocks, "one partial-sum slot per wave");
 
@@ -1153,11 +1153,12 @@ hipError_t launch_quantize_both(const QuantBothArgs& a, hipStream_t s)
     const int64_t nrb = a.rows / kBlock;
     const int rbu = a.fmt_c == kFP8 ? kRowBlocksPerUnit : 2 * kRowBlocksPerUnit;           // as in quant_both_kernel
     const int64_t units = ((a.cols + kColsPerWave - 1) / kColsPerWave) * ((nrb + rbu - 1) / rbu);
-    // Few units: one workgroup per unit, its four waves sharing the unit's tiles (measured: pays up to 1024 units
-    // of four tiles and 2048 units of eight); otherwise one wave per unit.  SNIP_QUANT_BOTH_UNIT=wave|workgroup in
-    // the environment, read at every call, fixes the choice for tests and measurements (the workgroup form only up
-    // to the number of partial-sum slots).
-    bool coop = units <= (a.fmt_c == kFP8 ? kCoopMaxUnits : 2 * kCoopMaxUnits);
+    // Few units: one workgroup per unit, its four waves sharing the unit's tiles; otherwise one wave per unit.
+    // Measured break-even: with statistics 1024 units of four tiles / 1536 units of eight, without statistics 2048
+    // units either way.  SNIP_QUANT_BOTH_UNIT=wave|workgroup in the environment, read at every call, fixes the
+    // choice for tests and measurements (the workgroup form only up to the number of partial-sum slots).
+    const int64_t coop_max = !st ? 2 * kCoopMaxUnits : (a.fmt_c == kFP8 ? kCoopMaxUnits : kCoopMaxUnits + kCoopMaxUnits / 2);
+    bool coop = units <= coop_max;
     if (const char* e = getenv("SNIP_QUANT_BOTH_UNIT")) {
         if (e[0] == 'w' && e[1] == 'a') coop = false;
         if (e[0] == 'w' && e[1] == 'o') coop = units <= kStreamBlocks;
