@@ -1122,10 +1122,9 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s)
     return e;
 }
 
-// Up to this many units (more in some modes, see launch_quantize_both) a tensor is quantized with one workgroup per
-// unit (COOP); the partial sums of that many workgroups fit the workspace (kStreamBlocks).
+// With the statistics of both formats: up to this many units of four tiles (half as many again of eight) a tensor is
+// quantized with one workgroup per unit (COOP), see launch_quantize_both.
 constexpr int kCoopMaxUnits = 1024;
-static_assert(2 * kCoopMaxUnits <= kStreamBlocks, "one partial-sum slot per wave");
 
 template <int FMT_R, int FMT_C, int RULE, int STATS>
 static void launch_qb(const QuantBothArgs& a, float* partials, int blocks, bool coop, hipStream_t s)
@@ -1153,18 +1152,19 @@ hipError_t launch_quantize_both(const QuantBothArgs& a, hipStream_t s)
     const int64_t nrb = a.rows / kBlock;
     const int rbu = a.fmt_c == kFP8 ? kRowBlocksPerUnit : 2 * kRowBlocksPerUnit;           // as in quant_both_kernel
     const int64_t units = ((a.cols + kColsPerWave - 1) / kColsPerWave) * ((nrb + rbu - 1) / rbu);
-    // Few units: one workgroup per unit, its four waves sharing the unit's tiles; otherwise one wave per unit.
-    // Measured break-even: with statistics 1024 units of four tiles / 1536 units of eight, without statistics 2048
-    // units either way.  SNIP_QUANT_BOTH_UNIT=wave|workgroup in the environment, read at every call, fixes the
-    // choice for tests and measurements (the workgroup form only up to the number of partial-sum slots).
-    const int64_t coop_max = !st ? 2 * kCoopMaxUnits : (a.fmt_c == kFP8 ? kCoopMaxUnits : kCoopMaxUnits + kCoopMaxUnits / 2);
-    bool coop = units <= coop_max;
+    // Work distribution.  One workgroup per unit (its four waves share the unit's tiles, 17 KB of LDS per workgroup,
+    // so more waves are resident) is the faster form except with the statistics of both formats, which fill the
+    // registers: there it pays only while a wave per unit would leave SIMDs without work (measured break-even: 1024
+    // units of four tiles, 1536 of eight).  SNIP_QUANT_BOTH_UNIT=wave|workgroup in the environment, read at every
+    // call, fixes the choice for tests and measurements.
+    const int mode = !st ? 0 : (a.both_formats ? 2 : 1);
+    bool coop = mode != 2 || units <= (a.fmt_c == kFP8 ? kCoopMaxUnits : kCoopMaxUnits + kCoopMaxUnits / 2);
     if (const char* e = getenv("SNIP_QUANT_BOTH_UNIT")) {
         if (e[0] == 'w' && e[1] == 'a') coop = false;
-        if (e[0] == 'w' && e[1] == 'o') coop = units <= kStreamBlocks;
+        if (e[0] == 'w' && e[1] == 'o') coop = true;
     }
-    const int blocks = coop ? (int)units : balanced_blocks(units);
-    const int mode = !st ? 0 : (a.both_formats ? 2 : 1);
+    // (a workgroup walks units blockIdx.x, blockIdx.x + gridDim.x, ...; the grid stays within the partial-sum slots)
+    const int blocks = coop ? (int)(units < kStreamBlocks ? units : kStreamBlocks) : balanced_blocks(units);
     const int key = (a.fmt_r << 4) | (a.fmt_c << 3) | (a.rule << 2) | mode;
     switch (key) {
 #define SNIP_QB_CASE(FR, FC, RU) \
