@@ -140,7 +140,11 @@ size_t snip_workspace_bytes(int64_t rows, int64_t cols);
  *   stats : device or NULL.  If given, the squared norms of x and of the quantization error
  *           of `fmt` are produced by the same pass (then `workspace` is required).
  *   workspace: device, >= snip_workspace_bytes(rows, cols) bytes, 16-byte aligned; may be
- *           NULL when stats is NULL. */
+ *           NULL when stats is NULL.
+ * Column-block calls are worked on by one workgroup per 128-column unit; the environment variable
+ * SNIP_QUANT_COL_UNIT=wave|workgroup, read at every call, fixes the work distribution for tests and
+ * measurements (codes and scales do not depend on it; fused statistics are summed in another
+ * fixed order). */
 snip_status snip_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld,
                           snip_fmt fmt, snip_axis axis, snip_scale_rule rule,
                           const snip_qtensor* out, snip_stats* stats,

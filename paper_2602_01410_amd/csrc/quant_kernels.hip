@@ -483,7 +483,10 @@ __device__ __forceinline__ unsigned quant_one_column(const unsigned* w, unsigned
     return byte;
 }
 
-template <int FMT, int RULE, bool STATS, bool SR = false>
+// COOP: the four waves of a workgroup share one unit (wave w takes its row blocks w, w + 4) and one staging area, so
+// that a workgroup needs 17 KB of LDS instead of 64 KB and more waves are resident; the scale bytes of the four row
+// blocks of a dword meet in LDS.  Same bytes out.
+template <int FMT, int RULE, bool STATS, bool SR = false, bool COOP = false>
 __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restrict__ x, int rows,
                                                         int cols, int64_t ld,
                                                         uint8_t* __restrict__ codes,
@@ -497,10 +500,12 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
     constexpr int RBU = FMT == kFP8 ? 4 : (SR ? 4 : 8);
     constexpr int ROWB = RBU * (FMT == kFP8 ? 32 : 16);   // staged output bytes per stored row
     constexpr int CPR = ROWB / 16;
-    __shared__ __attribute__((aligned(16))) uint8_t stage[kWavesPerBlock][kColsPerWave * ROWB];
+    __shared__ __attribute__((aligned(16))) uint8_t stage[COOP ? 1 : kWavesPerBlock][kColsPerWave * ROWB];
+    __shared__ __attribute__((aligned(4))) uint8_t scale_stage[COOP ? RBU * kColsPerWave : 4];   // COOP: scale byte of (row block, column)
     const int lane = threadIdx.x & 63;
-    uint8_t* const reg = stage[threadIdx.x >> 6];
-    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint8_t* const reg = stage[COOP ? 0 : wib];
+    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + wib);
     const int nwaves = gridDim.x * kWavesPerBlock;
     const int ncg = (cols + kColsPerWave - 1) / kColsPerWave;
     const int nrb = rows / kBlock;
@@ -508,46 +513,72 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
     const int units = ncg * nru;
     const int64_t out_row_bytes = FMT == kFP8 ? rows : rows / 2;
     float s0 = 0.f, se = 0.f;
-    for (int u = wave; u < units; u += nwaves) {
+    for (int u = COOP ? (int)blockIdx.x : wave; u < units; u += COOP ? (int)gridDim.x : nwaves) {
         const int ru = u / ncg, cg = u - ru * ncg;
         const int c = cg * kColsPerWave + lane * 2;
         const bool act = c < cols;
         const int rb0 = ru * RBU;
         const int nb = min(nrb - rb0, RBU);
         const int swz_lo = lane & (CPR - 1);          // ((2 * lane) >> 1) & (CPR - 1); the odd row shares it
-        // Four row blocks at a time: their scale bytes of a column form one dword of the row-major array (when
-        // the row length allows it) and exactly one dword of the grouped copy.
-        for (int h = 0; h < RBU / kRowBlocksPerUnit; ++h) {
-            const int nbh = min(nb - h * kRowBlocksPerUnit, kRowBlocksPerUnit);
-            if (nbh <= 0) break;
-            const int rbh = rb0 + h * kRowBlocksPerUnit;
-            unsigned g4_lo = 0, g4_hi = 0;
-            for (int k = 0; k < nbh; ++k) {
-                ColBlock b;
-                load_col_block(x + (int64_t)(rbh + k) * kBlock * ld + c, ld, act, b);
-                const int64_t e0 = (int64_t)c * rows + (int64_t)(rbh + k) * kBlock;       // stored row = source column
-                const int kk = h * kRowBlocksPerUnit + k;
-                const unsigned y0 = quant_one_column<FMT, RULE, STATS, SR>(b.lo, b.am_lo, reg + (2 * lane) * ROWB, kk, swz_lo, s0, se, e0, seed);
-                const unsigned y1 = quant_one_column<FMT, RULE, STATS, SR>(b.hi, b.am_hi, reg + (2 * lane + 1) * ROWB, kk, swz_lo, s0, se, e0 + rows, seed);
-                g4_lo |= y0 << (8 * k);
-                g4_hi |= y1 << (8 * k);
-            }
+        // row block kk of the unit: codes into the staging area, returns the two columns' scale bytes
+        auto one_block = [&](int kk, unsigned& y0, unsigned& y1) {
+            ColBlock b;
+            load_col_block(x + (int64_t)(rb0 + kk) * kBlock * ld + c, ld, act, b);
+            const int64_t e0 = (int64_t)c * rows + (int64_t)(rb0 + kk) * kBlock;       // stored row = source column
+            y0 = quant_one_column<FMT, RULE, STATS, SR>(b.lo, b.am_lo, reg + (2 * lane) * ROWB, kk, swz_lo, s0, se, e0, seed);
+            y1 = quant_one_column<FMT, RULE, STATS, SR>(b.hi, b.am_hi, reg + (2 * lane + 1) * ROWB, kk, swz_lo, s0, se, e0 + rows, seed);
+        };
+        // Four row blocks at a time (blocks 0 .. last of the group starting at rbh): their scale bytes of a column
+        // form one dword of the row-major array (when the row length allows it) and exactly one dword of the
+        // grouped copy.
+        auto store_scales = [&](int rbh, int last, unsigned lo, unsigned hi) {
             if (act) {
                 uint8_t* s_lo = scales + (int64_t)c * nrb + rbh;
                 if ((nrb & 3) == 0) {
-                    *reinterpret_cast<unsigned*>(s_lo) = g4_lo;
-                    *reinterpret_cast<unsigned*>(s_lo + nrb) = g4_hi;
+                    *reinterpret_cast<unsigned*>(s_lo) = lo;
+                    *reinterpret_cast<unsigned*>(s_lo + nrb) = hi;
                 } else {
-                    for (int k = 0; k < nbh; ++k) { s_lo[k] = (uint8_t)(g4_lo >> (8 * k)); s_lo[nrb + k] = (uint8_t)(g4_hi >> (8 * k)); }
+                    for (int k = 0; k <= last; ++k) { s_lo[k] = (uint8_t)(lo >> (8 * k)); s_lo[nrb + k] = (uint8_t)(hi >> (8 * k)); }
                 }
                 if (scales_g4)
-                    *reinterpret_cast<uint2*>(scales_g4 + ((int64_t)(rbh / kRowBlocksPerUnit) * kpitch + c) * 4) = make_uint2(g4_lo, g4_hi);
+                    *reinterpret_cast<uint2*>(scales_g4 + ((int64_t)(rbh / kRowBlocksPerUnit) * kpitch + c) * 4) = make_uint2(lo, hi);
+            }
+        };
+        if (COOP) {
+            for (int kk = wib; kk < nb; kk += kWavesPerBlock) {
+                unsigned y0, y1;
+                one_block(kk, y0, y1);
+                *reinterpret_cast<uint16_t*>(scale_stage + kk * kColsPerWave + 2 * lane) = (uint16_t)(y0 | (y1 << 8));
+            }
+            __syncthreads();                                   // all row blocks of the unit are staged
+            for (int h = wib; h * kRowBlocksPerUnit < nb; h += kWavesPerBlock) {
+                const int last = min(kRowBlocksPerUnit - 1, nb - 1 - h * kRowBlocksPerUnit);
+                unsigned lo = 0, hi = 0;
+                for (int k = 0; k <= last; ++k) {
+                    const unsigned v = *reinterpret_cast<const uint16_t*>(scale_stage + (h * kRowBlocksPerUnit + k) * kColsPerWave + 2 * lane);
+                    lo |= (v & 0xFFu) << (8 * k);
+                    hi |= (v >> 8) << (8 * k);
+                }
+                store_scales(rb0 + h * kRowBlocksPerUnit, last, lo, hi);
+            }
+        } else {
+            for (int h = 0; h < RBU / kRowBlocksPerUnit; ++h) {
+                const int nbh = min(nb - h * kRowBlocksPerUnit, kRowBlocksPerUnit);
+                if (nbh <= 0) break;
+                unsigned g4_lo = 0, g4_hi = 0;
+                for (int k = 0; k < nbh; ++k) {
+                    unsigned y0, y1;
+                    one_block(h * kRowBlocksPerUnit + k, y0, y1);
+                    g4_lo |= y0 << (8 * k);
+                    g4_hi |= y1 << (8 * k);
+                }
+                store_scales(rb0 + h * kRowBlocksPerUnit, nbh - 1, g4_lo, g4_hi);
             }
         }
         // Codes: read the staged image back row-contiguous and store 16 bytes per lane, so that every store
         // instruction writes whole ROWB-byte runs of 64 / CPR stored rows.
 #pragma unroll
-        for (int it = 0; it < kColsPerWave * CPR / 64; ++it) {
+        for (int it = COOP ? wib : 0; it < kColsPerWave * CPR / 64; it += COOP ? kWavesPerBlock : 1) {
             const int idx = it * 64 + lane;
             const int row = idx / CPR, chunk = idx % CPR;
             const uint4 v = *reinterpret_cast<const uint4*>(reg + row * ROWB + ((chunk ^ ((row >> 1) & (CPR - 1))) * 16));
@@ -556,6 +587,7 @@ __global__ __launch_bounds__(256) void quant_col_kernel(const uint16_t* __restri
             if (cc < cols && blk < nb)
                 *reinterpret_cast<uint4*>(codes + (int64_t)cc * out_row_bytes + (int64_t)ru * ROWB + chunk * 16) = v;
         }
+        if (COOP) __syncthreads();                             // the staging areas go to the next unit
     }
     if (STATS) {
         s0 = wave_sum(s0);
@@ -1074,10 +1106,22 @@ static int launch_q(const QuantArgs& a, float* partials, hipStream_t s)
     } else {
         const int64_t nrb = a.rows / kBlock;
         const int rbu = (FMT == kFP8 || SR) ? kRowBlocksPerUnit : 2 * kRowBlocksPerUnit;       // as in quant_col_kernel
-        blocks = balanced_blocks(((a.cols + kColsPerWave - 1) / kColsPerWave) * ((nrb + rbu - 1) / rbu));
-        hipLaunchKernelGGL((quant_col_kernel<FMT, RULE, STATS, SR>), dim3(blocks), dim3(256), 0, s,
-                           a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, a.scales_g4,
-                           g4_pitch(a.cols), partials, seed);
+        const int64_t units = ((a.cols + kColsPerWave - 1) / kColsPerWave) * ((nrb + rbu - 1) / rbu);
+        // a workgroup per unit (see quant_col_kernel); SNIP_QUANT_COL_UNIT=wave|workgroup, read at every call, fixes
+        // the choice for tests and measurements
+        bool coop = true;
+        if (const char* e = getenv("SNIP_QUANT_COL_UNIT")) coop = !(e[0] == 'w' && e[1] == 'a');
+        if (coop) {
+            blocks = (int)(units < kStreamBlocks ? units : kStreamBlocks);
+            hipLaunchKernelGGL((quant_col_kernel<FMT, RULE, STATS, SR, true>), dim3(blocks), dim3(256), 0, s,
+                               a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, a.scales_g4,
+                               g4_pitch(a.cols), partials, seed);
+        } else {
+            blocks = balanced_blocks(units);
+            hipLaunchKernelGGL((quant_col_kernel<FMT, RULE, STATS, SR, false>), dim3(blocks), dim3(256), 0, s,
+                               a.x, (int)a.rows, (int)a.cols, a.ld, a.codes, a.scales, a.scales_g4,
+                               g4_pitch(a.cols), partials, seed);
+        }
     }
     return blocks;
 }

@@ -26,3 +26,11 @@ def quant_both_unit(request, monkeypatch):
     128-column unit): the library reads SNIP_QUANT_BOTH_UNIT at every call."""
     monkeypatch.setenv("SNIP_QUANT_BOTH_UNIT", request.param)
     return request.param
+
+
+@pytest.fixture(params=["wave", "workgroup"])
+def quant_col_unit(request, monkeypatch):
+    """Runs a test of the column-block quantize once per work distribution (a wave or a workgroup per 128-column
+    unit): the library reads SNIP_QUANT_COL_UNIT at every call."""
+    monkeypatch.setenv("SNIP_QUANT_COL_UNIT", request.param)
+    return request.param

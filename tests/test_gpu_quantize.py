@@ -8,7 +8,7 @@ from paper_2602_01410_amd import workloads as wl
 
 from gpu_util import host, require_gpu, to_dev
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("quant_col_unit")]
 
 FMTS = [oracle.FP8, oracle.FP4]
 AXES = [oracle.ROW, oracle.COL]

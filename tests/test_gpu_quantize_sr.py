@@ -11,7 +11,7 @@ from paper_2602_01410_amd import workloads as wl
 from gpu_util import host, require_gpu, to_dev
 from test_gpu_quantize import wide_range_bits
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("quant_col_unit")]
 
 
 @pytest.mark.parametrize("axis", [oracle.ROW, oracle.COL])
