@@ -28,7 +28,7 @@ PEAK = {"fp4": 10.1e15, "fp8": 5.0e15, "hbm": 8.0e12}
 # L2-miss-side bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated against a copy kernel) of the dominant kernel.
 # Not measured by this run: counters need rocprofv3.  The figure is copied from the profile summary named beside
 # it, taken with this command on this kernel; a (config, plan, kernel) without such a profile reports null.
-MEASURED_TRAFFIC = {(4, "mix50", "gemm_fast_kernel<fp4,fp4>"): 546.5e6}
+MEASURED_TRAFFIC = {(4, "mix50", "gemm_fast_kernel<fp4,fp4>"): 546.6e6}
 TRAFFIC_SOURCE = "profiles/hbm_traffic_config4_mix50.md"
 KERNEL_NAME = {(0, 0): "gemm_fast_kernel<fp8,fp8>", (1, 1): "gemm_fast_kernel<fp4,fp4>",
                (0, 1): "gemm_fast_kernel<fp8,fp4>", (1, 0): "gemm_fast_kernel<fp4,fp8>"}
