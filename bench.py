@@ -52,7 +52,7 @@ def parse():
                    help="one quantize call per orientation (two reads of a tensor wanted in both) instead of snip_quantize_both")
     p.add_argument("--library-reference", action="store_true",
                    help="time the vendor library's GEMMs beside snip_gemm_fwd on the 7B shapes, print JSON and exit")
-    p.add_argument("--microbench", nargs="?", const="default", default=None, choices=["default", "hbm-sweep", "lds"],
+    p.add_argument("--microbench", nargs="?", const="default", default=None, choices=["default", "hbm-sweep", "lds", "mfma-lds"],
                    help="run the device microbenchmarks (measured MFMA / HBM / L2 rates; `hbm-sweep`: copy / read / write "
                         "rates over launch shapes, loads in flight, access widths and non-temporal hints) and exit")
     return p.parse_args()

@@ -221,8 +221,73 @@ static int lds_bench()
     return 0;
 }
 
+// MFMA issue rate with LDS reads going on beside it: every wave (8 per CU) issues 16 MFMAs on random operands that
+// change every instruction, then READS ds_read_b128 of random LDS data, as a GEMM wave does per phase; the data read
+// is only folded into a checksum.  Shows what the LDS -> register traffic of a tiling costs the matrix cores.
+template <int FMT, int READS>
+__global__ __launch_bounds__(512) void k_mfma_lds(const int* __restrict__ rnd, float* out, int iters)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[65536];
+    for (int i = threadIdx.x; i < 65536 / 4; i += blockDim.x) ((int*)lds)[i] = rnd[i & 16383];
+    __syncthreads();
+    v8i a[4], b[4];
+    for (int j = 0; j < 4; ++j)
+        for (int i = 0; i < 8; ++i) {
+            const int ia = (threadIdx.x * 8 + i + j * 2048) & 16383;
+            a[j][i] = rnd[ia];
+            b[j][i] = rnd[(ia + 8192) & 16383];
+            if (FMT == 0) { a[j][i] &= 0x77777777; b[j][i] &= 0x77777777; }
+        }
+    v16f acc[4];
+    for (int n = 0; n < 4; ++n) for (int i = 0; i < 16; ++i) acc[n][i] = 0;
+    unsigned chk = 0, off = (threadIdx.x & 63) * 16 + (threadIdx.x >> 6) * 1024;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int n = 0; n < 4; ++n)
+                acc[n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[(n + r) & 3], b[(n + 2 * r + 1) & 3], acc[n], FMT, FMT, 0, 120, 0, 120);
+#pragma unroll
+        for (int u = 0; u < READS; ++u) {
+            const uint4 v = *(const uint4*)(lds + ((off + u * 8192) & 65535u));
+            chk ^= v.x ^ v.y ^ v.z ^ v.w;
+        }
+        off += 1024;
+    }
+    float s = 0;
+    for (int n = 0; n < 4; ++n) for (int i = 0; i < 16; ++i) s += acc[n][i];
+    out[blockIdx.x * 512 + threadIdx.x] = s + (chk == 0x12345678u ? 1.f : 0.f);
+}
+
+template <int FMT> static void mfma_lds_row(const int* rnd, float* out, const char* name)
+{
+    const int iters = 4000;
+    const double fl = 512.0 * 8 * iters * 16 * 2.0 * 32 * 32 * 64;
+    float ms;
+    ms = time_ms([&] { k_mfma_lds<FMT, 0><<<512, 512>>>(rnd, out, iters); }, 2);  printf("\"%s_reads0_tflops\": %.1f, ", name, fl / ms / 1e9);
+    ms = time_ms([&] { k_mfma_lds<FMT, 4><<<512, 512>>>(rnd, out, iters); }, 2);  printf("\"%s_reads4_tflops\": %.1f, ", name, fl / ms / 1e9);
+    ms = time_ms([&] { k_mfma_lds<FMT, 8><<<512, 512>>>(rnd, out, iters); }, 2);  printf("\"%s_reads8_tflops\": %.1f, ", name, fl / ms / 1e9);
+    ms = time_ms([&] { k_mfma_lds<FMT, 12><<<512, 512>>>(rnd, out, iters); }, 2); printf("\"%s_reads12_tflops\": %.1f, ", name, fl / ms / 1e9);
+    ms = time_ms([&] { k_mfma_lds<FMT, 24><<<512, 512>>>(rnd, out, iters); }, 2); printf("\"%s_reads24_tflops\": %.1f", name, fl / ms / 1e9);
+}
+
+static int mfma_lds_bench()
+{
+    int* rnd; CK(hipMalloc(&rnd, 16384 * 4));
+    static int h[16384]; srand(1); for (int i = 0; i < 16384; ++i) h[i] = rand() ^ (rand() << 16);
+    CK(hipMemcpy(rnd, h, sizeof h, hipMemcpyHostToDevice));
+    float* out; CK(hipMalloc(&out, 512 * 512 * 4));
+    printf("{");
+    mfma_lds_row<4>(rnd, out, "fp4");
+    printf(", ");
+    mfma_lds_row<0>(rnd, out, "fp8");
+    printf("}\n");
+    return 0;
+}
+
 int main(int argc, char** argv)
 {
+    if (argc > 1 && std::string(argv[1]) == "mfma-lds") return mfma_lds_bench();
     if (argc > 1 && std::string(argv[1]) == "lds") return lds_bench();
     if (argc > 1 && std::string(argv[1]) == "hbm-sweep") return hbm_sweep();
     int* rnd; CK(hipMalloc(&rnd, 16384 * 4));
