@@ -10,6 +10,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <string>
+#include <vector>
 #define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); exit(2);} } while (0)
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -224,10 +225,11 @@ static int lds_bench()
 // MFMA issue rate with LDS reads going on beside it: every wave (8 per CU) issues 16 MFMAs on random operands that
 // change every instruction, then READS ds_read_b128 of random LDS data, as a GEMM wave does per phase; the data read
 // is only folded into a checksum.  Shows what the LDS -> register traffic of a tiling costs the matrix cores.
-template <int FMT, int READS>
-__global__ __launch_bounds__(512) void k_mfma_lds(const int* __restrict__ rnd, float* out, int iters)
+template <int FMT, int READS, int COPIES = 0>
+__global__ __launch_bounds__(512) void k_mfma_lds(const int* __restrict__ rnd, float* out, int iters,
+                                                  const uint8_t* __restrict__ src = nullptr, size_t region_bytes = 0)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[65536];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[65536 + (COPIES ? 65536 : 0)];
     for (int i = threadIdx.x; i < 65536 / 4; i += blockDim.x) ((int*)lds)[i] = rnd[i & 16383];
     __syncthreads();
     v8i a[4], b[4];
@@ -241,12 +243,23 @@ __global__ __launch_bounds__(512) void k_mfma_lds(const int* __restrict__ rnd, f
     v16f acc[4];
     for (int n = 0; n < 4; ++n) for (int i = 0; i < 16; ++i) acc[n][i] = 0;
     unsigned chk = 0, off = (threadIdx.x & 63) * 16 + (threadIdx.x >> 6) * 1024;
+    // COPIES global -> LDS copies of 1 KB per wave and iteration into a second 64 KB area, from a region that stays
+    // in the memory-side caches (what a GEMM wave issues per phase for its share of the next stage)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned cbase = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)lds + 65536 + wave * 8192;
+    size_t goff = COPIES ? ((size_t)blockIdx.x * 7919 * 8192 + wave * 1024 + (threadIdx.x & 63) * 16) % region_bytes : 0;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
-            for (int n = 0; n < 4; ++n)
+            for (int n = 0; n < 4; ++n) {
                 acc[n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[(n + r) & 3], b[(n + 2 * r + 1) & 3], acc[n], FMT, FMT, 0, 120, 0, 120);
+                if (COPIES && (r * 4 + n) < COPIES) {
+                    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src + goff), "s"(cbase + ((r * 4 + n) & 7) * 1024) : "memory", "m0");
+                    goff += 8192; if (goff >= region_bytes) goff -= region_bytes;
+                }
+            }
+        if (COPIES && (it & 1)) __builtin_amdgcn_s_waitcnt(0x0F70 | (COPIES < 15 ? COPIES : 15));   // at most one iteration's copies in flight
 #pragma unroll
         for (int u = 0; u < READS; ++u) {
             const uint4 v = *(const uint4*)(lds + ((off + u * 8192) & 65535u));
@@ -254,12 +267,13 @@ __global__ __launch_bounds__(512) void k_mfma_lds(const int* __restrict__ rnd, f
         }
         off += 1024;
     }
+    if (COPIES) __builtin_amdgcn_s_waitcnt(0x0F70);
     float s = 0;
     for (int n = 0; n < 4; ++n) for (int i = 0; i < 16; ++i) s += acc[n][i];
     out[blockIdx.x * 512 + threadIdx.x] = s + (chk == 0x12345678u ? 1.f : 0.f);
 }
 
-template <int FMT> static void mfma_lds_row(const int* rnd, float* out, const char* name)
+template <int FMT> static void mfma_lds_row(const int* rnd, float* out, const char* name, const uint8_t* src)
 {
     const int iters = 4000;
     const double fl = 512.0 * 8 * iters * 16 * 2.0 * 32 * 32 * 64;
@@ -268,7 +282,14 @@ template <int FMT> static void mfma_lds_row(const int* rnd, float* out, const ch
     ms = time_ms([&] { k_mfma_lds<FMT, 4><<<512, 512>>>(rnd, out, iters); }, 2);  printf("\"%s_reads4_tflops\": %.1f, ", name, fl / ms / 1e9);
     ms = time_ms([&] { k_mfma_lds<FMT, 8><<<512, 512>>>(rnd, out, iters); }, 2);  printf("\"%s_reads8_tflops\": %.1f, ", name, fl / ms / 1e9);
     ms = time_ms([&] { k_mfma_lds<FMT, 12><<<512, 512>>>(rnd, out, iters); }, 2); printf("\"%s_reads12_tflops\": %.1f, ", name, fl / ms / 1e9);
-    ms = time_ms([&] { k_mfma_lds<FMT, 24><<<512, 512>>>(rnd, out, iters); }, 2); printf("\"%s_reads24_tflops\": %.1f", name, fl / ms / 1e9);
+    ms = time_ms([&] { k_mfma_lds<FMT, 24><<<512, 512>>>(rnd, out, iters); }, 2); printf("\"%s_reads24_tflops\": %.1f, ", name, fl / ms / 1e9);
+    // the GEMM's own mix per wave and 16 MFMAs: FP4 12 reads + 5 copies, FP8 24 reads + 9 copies (codes and scales of a
+    // 256 x 256 tile: 68 / 66 KB per stage over 8 waves); copies from a 2 MB region (L2 hits: the cheapest case)
+    constexpr int R = FMT == 4 ? 12 : 24, C = FMT == 4 ? 5 : 9;
+    ms = time_ms([&] { k_mfma_lds<FMT, R, C><<<512, 512>>>(rnd, out, iters, src, (size_t)2 << 20); }, 2);
+    printf("\"%s_gemm_mix_reads%d_copies%d_tflops\": %.1f, ", name, R, C, fl / ms / 1e9);
+    ms = time_ms([&] { k_mfma_lds<FMT, 0, C><<<512, 512>>>(rnd, out, iters, src, (size_t)2 << 20); }, 2);
+    printf("\"%s_reads0_copies%d_tflops\": %.1f", name, C, fl / ms / 1e9);
 }
 
 static int mfma_lds_bench()
@@ -277,10 +298,16 @@ static int mfma_lds_bench()
     static int h[16384]; srand(1); for (int i = 0; i < 16384; ++i) h[i] = rand() ^ (rand() << 16);
     CK(hipMemcpy(rnd, h, sizeof h, hipMemcpyHostToDevice));
     float* out; CK(hipMalloc(&out, 512 * 512 * 4));
+    uint8_t* src; CK(hipMalloc((void**)&src, (size_t)64 << 20));
+    {   // random bytes in the copy source as well
+        std::vector<int> big(((size_t)64 << 20) / 4);
+        for (size_t i = 0; i < big.size(); ++i) big[i] = h[i & 16383] * (int)(2 * i + 1);
+        CK(hipMemcpy(src, big.data(), (size_t)64 << 20, hipMemcpyHostToDevice));
+    }
     printf("{");
-    mfma_lds_row<4>(rnd, out, "fp4");
+    mfma_lds_row<4>(rnd, out, "fp4", src);
     printf(", ");
-    mfma_lds_row<0>(rnd, out, "fp8");
+    mfma_lds_row<0>(rnd, out, "fp8", src);
     printf("}\n");
     return 0;
 }
